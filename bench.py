@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the MMM hot path on one MI355X.
+
+A step is one pass of the whole path on device-resident inputs:
+mmm_build_maps (both sides) followed by mmm_matmul.  The default workload is
+the benchmark's configs[1] (M=K=N=2048 fp32, 90 % zeros in A, 90 % empty 16-wide
+blocks in B).  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg3:<i>|cfg4|cfg5]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def parse_workload(name):
+    import mmm_synth as synth
+    if name.startswith("cfg3"):
+        ip = int(name.split(":")[1]) if ":" in name else 3
+        return synth.config(3, ip)
+    return synth.config(int(name[3:]))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--variant", type=int, default=-1)
+    ap.add_argument("--split-k", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards without communication, "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import mmm_synth as synth
+    import paper_2402_14118_amd as mm
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    w = parse_workload(args.workload)
+    esz = 2 if w.dtype == synth.DT_BF16 else 4
+
+    def up(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    if w.dtype == synth.DT_BF16:
+        X, Y = up(w.X_bits.view(np.int16)), up(w.Y_bits.view(np.int16))
+    else:
+        X, Y = up(w.X), up(w.Y)
+    keep_a = None if w.keep_a is None else up(w.keep_a.view(np.int64))
+    keep_rows = None if w.keep_rows is None else up(w.keep_rows.view(np.int64))
+    keep_blocks = None if w.keep_blocks is None else up(w.keep_blocks.view(np.int64))
+    C = torch.empty((w.M, w.N), dtype=torch.float32, device="cuda")
+    eng = mm.MaskedMatmul(w.M, w.K, w.N, w.bw, w.dtype)
+    mm.mmm_set_option("matmul_variant", args.variant)
+    mm.mmm_set_option("split_k", args.split_k)
+
+    def build():
+        eng.build_maps(X, Y, w.pred, w.threshold, keep_a, keep_rows, keep_blocks)
+
+    def matmul():
+        eng.matmul(X, Y, C)
+
+    build()
+    matmul()
+    nnz_a, occ_b, useful_macs = eng.stats()
+    variant, split_k, workgroups = eng.plan()
+
+    for _ in range(args.warmup):
+        build()
+        matmul()
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` steps; per-kernel durations from events on the launch stream
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        ev[i][0].record()
+        build()
+        ev[i][1].record()
+        matmul()
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3
+    ms_per_step = wall_ms / K
+    build_ms = np.array([ev[i][0].elapsed_time(ev[i][1]) for i in range(K)])
+    matmul_ms = np.array([ev[i][1].elapsed_time(ev[i][2]) for i in range(K)])
+    t_build, t_matmul = float(build_ms.mean()), float(matmul_ms.mean())
+
+    useful_flops = 2.0 * useful_macs
+    dense_flops = 2.0 * w.M * w.K * w.N
+    value = useful_flops / (ms_per_step * 1e-3) / 1e9
+
+    # algorithmic bytes of one launch (what the method itself must move)
+    WA, NB = (w.K + 63) // 64, w.N // w.bw
+    WB = (NB + 63) // 64
+    map_bytes = w.M * WA * 8 + ((w.M + 31) // 32) * WA * 8 + w.K * WB * 8 + NB * WA * 8
+    kept_blocks = occ_b if w.keep_blocks is None and w.keep_rows is None else None
+    if kept_blocks is None:     # blocks the keep bitmaps leave switched on are the ones the builder must read
+        kb = np.ones((w.K, NB), dtype=bool)
+        if w.keep_rows is not None:
+            kb &= synth.unpack_bits(w.keep_rows.reshape(1, -1), w.K)[0][:, None]
+        if w.keep_blocks is not None:
+            kb &= synth.unpack_bits(w.keep_blocks, NB)
+        kept_blocks = int(kb.sum())
+    build_bytes = w.M * w.K * esz + kept_blocks * w.bw * esz + map_bytes
+    matmul_bytes = w.M * w.K * esz + occ_b * w.bw * esz + map_bytes + w.M * w.N * 4
+    dominant = "mmm_matmul_kernel" if t_matmul >= t_build else "mmm_build_kernel"
+    dom_ms = max(t_matmul, t_build)
+    dom_bytes = matmul_bytes if t_matmul >= t_build else build_bytes
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "algorithmic_bytes": dom_bytes, "avg_launch_us": dom_ms * 1e3,
+                "build": {"avg_launch_us": t_build * 1e3, "algorithmic_bytes": build_bytes,
+                          "achieved_GBs": build_bytes / (t_build * 1e-3) / 1e9},
+                "matmul": {"avg_launch_us": t_matmul * 1e3, "algorithmic_bytes": matmul_bytes,
+                           "achieved_GBs": matmul_bytes / (t_matmul * 1e-3) / 1e9,
+                           "useful_TFLOPs": useful_flops / (t_matmul * 1e-3) / 1e12,
+                           "useful_frac_of_fp32_vector_peak": useful_flops / (t_matmul * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS}}
+
+    out = {
+        "metric": "useful_gflops", "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": K,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if w.dtype == synth.DT_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "block_width": w.bw,
+                   "nnz_a": nnz_a, "occupied_blocks_b": occ_b, "useful_macs": useful_macs,
+                   "a_density": nnz_a / (w.M * w.K), "b_block_density": occ_b / (w.K * NB),
+                   "variant": mm.mmm_matmul_variant_name(variant), "split_k": split_k, "workgroups": workgroups},
+        "dense_equivalent_gflops": dense_flops / (ms_per_step * 1e-3) / 1e9,
+        "t_build_us": t_build * 1e3, "t_matmul_us": t_matmul * 1e3,
+        "roofline": roofline,
+    }
+
+    if not args.no_dense:
+        # comparison point only: a dense GEMM of the materialised masked operands, same dtype
+        def unpack(bits, cols):     # device bitmap [rows, words] int64 -> bool [rows, cols]
+            sh = torch.arange(64, device="cuda", dtype=torch.int64)
+            return (((bits.unsqueeze(-1) >> sh) & 1) != 0).reshape(bits.shape[0], -1)[:, :cols]
+
+        torch.cuda.synchronize()
+        Xf = X if w.dtype != synth.DT_BF16 else (X.to(torch.int32) << 16).view(torch.float32)
+        Yf = Y if w.dtype != synth.DT_BF16 else (Y.to(torch.int32) << 16).view(torch.float32)
+        A = torch.where(unpack(eng.a_bits(), w.K), Xf, torch.zeros((), device="cuda"))
+        B = torch.where(unpack(eng.b_bits(), NB).repeat_interleave(w.bw, dim=1), Yf, torch.zeros((), device="cuda"))
+        if w.dtype == synth.DT_BF16:
+            A, B = A.bfloat16(), B.bfloat16()
+        torch.backends.cuda.matmul.allow_tf32 = False
+        for _ in range(5):
+            D = torch.matmul(A, B)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(5, min(50, K))
+        e0.record()
+        for _ in range(reps):
+            D = torch.matmul(A, B)
+        e1.record()
+        torch.cuda.synchronize()
+        t_dense = e0.elapsed_time(e1) / reps
+        out["dense_gemm_ms"] = t_dense
+        out["dense_gemm_tflops"] = dense_flops / (t_dense * 1e-3) / 1e12
+        out["speedup_vs_dense"] = t_dense / ms_per_step
+        out["speedup_vs_dense_matmul_only"] = t_dense / t_matmul
+        del A, B, D
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # bounded sample: whole rows of C until about 10 s of CPU work; maps always in full
+        t = time.perf_counter()
+        ab = oracle.a_bits(w.X, w.pred, w.threshold, w.keep_a)
+        bb = oracle.b_bits(w.Y, w.bw, w.keep_rows, w.keep_blocks)
+        t_maps = time.perf_counter() - t
+        probe = max(1, min(w.M, 64))
+        t = time.perf_counter()
+        oracle.mmm(w.X, w.Y, ab, bb, w.bw, want_mag=False, rows=(0, probe))
+        t_probe = time.perf_counter() - t
+        rows = int(min(w.M, max(probe, 10.0 / max(t_probe / probe, 1e-9))))
+        t = time.perf_counter()
+        oracle.mmm(w.X, w.Y, ab, bb, w.bw, want_mag=False, rows=(0, rows))
+        t_rows = time.perf_counter() - t
+        a_rows = synth.unpack_bits(ab[:rows], w.K).sum(axis=0).astype(np.int64)
+        b_rows = synth.unpack_bits(bb, NB).sum(axis=1).astype(np.int64)
+        macs_sample = int((a_rows * b_rows).sum()) * w.bw
+        t_total = t_rows + t_maps * rows / w.M
+        out["cpu_baseline"] = {"value": 2.0 * macs_sample / t_total / 1e9, "unit": "GFLOP/s",
+                               "cores": oracle.threads(), "kind": "oracle",
+                               "sample": f"rows 0..{rows} of {w.M} (maps in full, pro-rated), {t_total:.2f} s",
+                               "ms_per_step_extrapolated": t_total * w.M / rows * 1e3}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,180 @@
+/*
+ * mmm.h -- C ABI of the MI355X (gfx950) Masked Matrix Multiplication engine.
+ *
+ *   C = M(X) x N(Y)
+ *
+ * X (M x K) and Y (K x N) are dense, row-major and live in device memory.  M and
+ * N are masks evaluated at run time: M zeroes single elements of X, N zeroes
+ * whole aligned 1 x block_width pieces of the rows of Y (paper, sections 1 and
+ * 3: A = M(X) has random element sparsity, B = N(Y) block-random sparsity; Fig.
+ * "Types of sparsity").  The work is split the way the paper splits it
+ * (section 3, "Preprocessing" and "Matrix Multiplication"): one pass builds
+ * sparsity maps, the multiplication then consumes the maps and skips every
+ * product whose A element is zero or whose B block is empty.
+ *
+ * Conventions for every call
+ *   - Pointers named X, Y, C, keep_*, dev_workspace are DEVICE pointers owned by
+ *     the caller.  The library never allocates or frees device memory and keeps
+ *     no pointer to X, Y or C after a call returns.
+ *   - Row-major; leading dimensions (ldx, ldy, ldc) are in elements and must be
+ *     >= the row length.  C is always float.
+ *   - Bitmaps: LSB-first little-endian 64-bit words, row-major, every row padded
+ *     to whole words, pad bits zero: bit (c mod 64) of word (c div 64) of row r
+ *     describes column c of row r.  (The paper prints patterns first-vector-
+ *     leftmost; the layout here is this library's own.)
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls enqueue work and return; only mmm_maps_stats waits for the stream.
+ *   - Errors are return codes.  Arguments are checked on the host before any
+ *     device work is enqueued; on error nothing is launched and no output is
+ *     touched.  No call aborts or prints.
+ *   - Inputs are assumed finite inside kept B blocks.  Masked-out elements of X
+ *     and blocks of Y never reach the arithmetic, whatever they hold.
+ */
+#ifndef MMM_H
+#define MMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MMM_OK = 0,
+    MMM_ERR_INVALID_ARG = 1,   /* NULL where a pointer is required, bad enum value                */
+    MMM_ERR_SHAPE = 2,         /* M, K, N < 1, ld too small, N not a multiple of block_width      */
+    MMM_ERR_DTYPE = 3,         /* unknown element type, or misaligned pointer for that type       */
+    MMM_ERR_WORKSPACE = 4,     /* workspace NULL, misaligned (256 B) or too small                 */
+    MMM_ERR_MAPS_MISMATCH = 5, /* maps not built yet, or built for another shape / element type   */
+    MMM_ERR_DEVICE = 6         /* a HIP call failed (launch error)                                */
+} mmm_status;
+
+/* Element type of X and Y.  BF16 is the upper half of an IEEE float. */
+typedef enum { MMM_F32 = 0, MMM_BF16 = 1 } mmm_dtype;
+
+/* Element predicate of M.  An element of A is non-zero iff the predicate holds,
+ * the optional keep bit is set, and the value is not +-0.  (Zero test by value:
+ * paper Fig. "skip computation when A is sparse".  ReLU sparsity, section 1, is
+ * MMM_PRED_GT with threshold 0.)  NaN fails MMM_PRED_GT and MMM_PRED_ABS_GT;
+ * denormals are non-zero. */
+typedef enum {
+    MMM_PRED_NONZERO = 0, /* x != 0        */
+    MMM_PRED_GT = 1,      /* x >  threshold */
+    MMM_PRED_ABS_GT = 2   /* |x| > threshold */
+} mmm_pred;
+
+/* M: element mask over X. */
+typedef struct {
+    int32_t pred;              /* mmm_pred */
+    float threshold;
+    const uint64_t *keep_bits; /* optional device bitmap, M x ceil(K/64) words, AND-ed with pred */
+} mmm_mask_a;
+
+/* N: block mask over Y.  A block is the aligned piece [jb*bw, jb*bw+bw) of one
+ * row.  A kept block is *occupied* iff it holds any non-zero value (paper,
+ * section 3, "Block-Random Sparsity in B"; caption of Fig. "Preprocessing
+ * patterns": bit 1 = some non-zero value). */
+typedef struct {
+    int32_t block_width;         /* 8, 16 or 32; must equal the width given to mmm_maps_init     */
+    const uint64_t *keep_rows;   /* optional device bitmap, ceil(K/64) words: whole rows of Y    */
+    const uint64_t *keep_blocks; /* optional device bitmap, K x ceil(NB/64) words, NB = N / bw   */
+} mmm_mask_b;
+
+/* Host-side handle describing maps that live in caller-provided device memory. */
+typedef struct mmm_maps mmm_maps;
+
+/* Bytes of device workspace that maps for this shape need (maps, their derived
+ * forms, and the partial-sum area of the split-K multiplication).
+ * Errors: MMM_ERR_SHAPE, MMM_ERR_INVALID_ARG (bytes NULL). */
+mmm_status mmm_maps_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t block_width, size_t *bytes);
+
+/* Create the handle.  `dev_workspace` must be 256-byte aligned device memory of
+ * at least mmm_maps_workspace_bytes(); it stays owned by the caller and must
+ * outlive the handle.  No device work is done here.  *out is written only on
+ * success.  Errors: MMM_ERR_SHAPE, MMM_ERR_WORKSPACE, MMM_ERR_INVALID_ARG. */
+mmm_status mmm_maps_init(void *dev_workspace, size_t workspace_bytes, int64_t M, int64_t K, int64_t N,
+                         int32_t block_width, mmm_maps **out);
+
+/* Frees the host handle only (NULL is allowed). */
+void mmm_maps_release(mmm_maps *maps);
+
+/* Evaluate the masks on the device and write the sparsity maps into the
+ * workspace (paper, section 3 "Preprocessing": one sequential, aligned pass per
+ * matrix; Fig. "Preprocessing function pointer arrays" for B, Fig. "Blocked
+ * sparse row preprocessing" for A -- here both become bitmaps):
+ *     a_bits[i,k]  = pred(X[i,k]) & keep_bits[i,k] & (X[i,k] != 0)
+ *     b_bits[k,jb] = keep_rows[k] & keep_blocks[k,jb] & (some Y[k, jb*bw .. jb*bw+bw) != 0)
+ * plus derived forms the multiplication reads (column-any words of A per 32-row
+ * tile, the B map transposed to one bit-row per block column).
+ * Either side may be skipped by passing X == NULL (then ma is ignored) or
+ * Y == NULL: that side's maps from an earlier call are kept -- the B side of a
+ * weight matrix is built once and reused (section 3: rows of B are preprocessed
+ * once and used many times).  Lanes of Y whose block is switched off by the keep
+ * bitmaps are not read.
+ * Errors: MMM_ERR_INVALID_ARG (maps NULL, both X and Y NULL, mask struct NULL for
+ * a present side, bad pred), MMM_ERR_SHAPE (ld too small, block_width differs
+ * from the handle's), MMM_ERR_DTYPE, MMM_ERR_DEVICE. */
+mmm_status mmm_build_maps(mmm_maps *maps, mmm_dtype dt,
+                          const void *X, int64_t ldx, const mmm_mask_a *ma,
+                          const void *Y, int64_t ldy, const mmm_mask_b *mb,
+                          void *hip_stream);
+
+/* Device pointers to the two primary maps, for inspection.  a_bits is
+ * M x *a_row_words words, b_bits is K x *b_row_words words.  Any out pointer may
+ * be NULL.  Valid once the side has been built and the stream has reached that
+ * point.  Errors: MMM_ERR_INVALID_ARG. */
+mmm_status mmm_maps_view(const mmm_maps *maps, const uint64_t **a_bits, int64_t *a_row_words,
+                         const uint64_t **b_bits, int64_t *b_row_words);
+
+/* Device pointers to the derived maps, for inspection:
+ *   a_colany: ceil(M/32) x ceil(K/64) words; bit k of row t = OR of a_bits[i,k], i in [32t, 32t+32)
+ *   bt_bits : NB x ceil(K/64) words; bit k of row jb = b_bits[k,jb]   (the B map transposed)
+ * Errors: MMM_ERR_INVALID_ARG. */
+mmm_status mmm_maps_view_derived(const mmm_maps *maps, const uint64_t **a_colany, const uint64_t **bt_bits,
+                                 int64_t *k_words);
+
+/* Counts taken from the maps (runs a small reduction on `hip_stream`, then
+ * WAITS for the stream): non-zeros of A, occupied blocks of B, and useful
+ * multiply-adds  sum_k nnz(A[:,k]) * bw * occupied(B[k,:])  -- the products the
+ * loop of Fig. "MMM Pseudocode" performs.  Any out pointer may be NULL.
+ * Errors: MMM_ERR_INVALID_ARG, MMM_ERR_MAPS_MISMATCH (a side not built),
+ * MMM_ERR_DEVICE. */
+mmm_status mmm_maps_stats(const mmm_maps *maps, uint64_t *nnz_a, uint64_t *occupied_blocks_b,
+                          uint64_t *useful_macs, void *hip_stream);
+
+/* C = A x B (accumulate == 0) or C += A x B (accumulate != 0) using the maps:
+ *     C[i,j] (+)= sum over k with a_bits[i,k] & b_bits[k, j div bw] of X[i,k] * Y[k,j]
+ * (paper, section 3 "Matrix Multiplication", Fig. "MMM Pseudocode").  X and Y
+ * must hold the same values the maps were built from.  Every element of C is
+ * written exactly once, zeros included.  float accumulation; the result is
+ * bitwise reproducible from run to run for the same inputs and shape.
+ * Errors: MMM_ERR_INVALID_ARG, MMM_ERR_SHAPE, MMM_ERR_DTYPE,
+ * MMM_ERR_MAPS_MISMATCH (a side not built, or dt differs from the build),
+ * MMM_ERR_DEVICE. */
+mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt,
+                      const void *X, int64_t ldx, const void *Y, int64_t ldy,
+                      float *C, int64_t ldc, int32_t accumulate, void *hip_stream);
+
+/* Process-wide tuning knobs (for benchmarking; the defaults choose by shape).
+ *   "matmul_variant": -1 = automatic, else index of a compiled tile variant
+ *   "split_k"       :  0 = automatic, else the number of K splits to use
+ * Errors: MMM_ERR_INVALID_ARG (unknown name or value out of range). */
+mmm_status mmm_set_option(const char *name, int64_t value);
+
+/* Number of compiled tile variants and a short description of variant i
+ * (NULL if i is out of range). */
+int32_t mmm_matmul_variant_count(void);
+const char *mmm_matmul_variant_name(int32_t i);
+
+/* The launch plan mmm_matmul would use for these maps: variant index, K splits,
+ * grid size.  Any out pointer may be NULL.  Errors: MMM_ERR_INVALID_ARG. */
+mmm_status mmm_matmul_plan(const mmm_maps *maps, mmm_dtype dt, int32_t *variant, int32_t *split_k,
+                           int64_t *workgroups);
+
+const char *mmm_status_string(mmm_status st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MMM_H */

@@ -1,0 +1,297 @@
+// Host side of the C ABI declared in include/mmm.h: argument checks, workspace
+// layout, launch planning.  All checks run before any device call, so they can
+// be exercised on a machine without a GPU.
+#include <atomic>
+#include <cstring>
+#include <new>
+
+#include "mmm_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr size_t kPartialCap = (size_t)64 << 20;   // split-K partial sums: at most 64 MiB
+
+std::atomic<int64_t> g_opt_variant{-1};
+std::atomic<int64_t> g_opt_split{0};
+
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+    size_t a_bits, a_colany, b_bits, bt_bits, stats, partials, partial_bytes, total;
+};
+
+bool shape_ok(int64_t M, int64_t K, int64_t N, int32_t bw)
+{
+    if (M < 1 || K < 1 || N < 1) return false;
+    if (bw != 8 && bw != 16 && bw != 32) return false;
+    if (N % bw != 0) return false;
+    // 31-bit grids and 16-bit chunk-relative indices are used throughout
+    if (M > (1LL << 30) || K > (1LL << 30) || N > (1LL << 30)) return false;
+    return true;
+}
+
+Layout make_layout(int64_t M, int64_t K, int64_t N, int32_t bw)
+{
+    const int64_t NB = N / bw, WA = (K + 63) / 64, WB = (NB + 63) / 64, MT = (M + MMM_COLANY_ROWS - 1) / MMM_COLANY_ROWS;
+    Layout l{};
+    size_t off = 0;
+    l.a_bits = off;
+    off += align_up((size_t)M * WA * 8);
+    l.a_colany = off;
+    off += align_up((size_t)MT * WA * 8);
+    l.b_bits = off;
+    off += align_up((size_t)K * WB * 8);
+    l.bt_bits = off;
+    off += align_up((size_t)NB * WA * 8);
+    l.stats = off;
+    off += align_up(4 * 8);
+    l.partials = off;
+    // room for up to 32 splits of C, capped
+    size_t want = (size_t)M * (size_t)N * sizeof(float) * 32;
+    if (want > kPartialCap) want = kPartialCap;
+    l.partial_bytes = align_up(want);
+    off += l.partial_bytes;
+    l.total = off;
+    return l;
+}
+
+bool dtype_ok(int32_t dt) { return dt == MMM_F32 || dt == MMM_BF16; }
+size_t elem_size(int32_t dt) { return dt == MMM_BF16 ? 2 : 4; }
+
+mmm_plan make_plan(const mmm_maps *m, int32_t dt)
+{
+    (void)dt;
+    mmm_plan p{};
+    int64_t v = g_opt_variant.load();
+    if (v < 0 || v >= mmm_variant_count()) {
+        // automatic: row tile from M, column tile from how many workgroups result
+        if (m->M <= 32) {
+            v = 2;
+        } else {
+            const int64_t t64x256 = ((m->M + 63) / 64) * ((m->N + 255) / 256);
+            v = t64x256 >= 1024 ? 0 : 1;
+        }
+    }
+    const mmm_variant_info &vi = mmm_variant((int32_t)v);
+    p.variant = (int32_t)v;
+    p.tiles_m = (int32_t)((m->M + vi.TM - 1) / vi.TM);
+    p.tiles_n = (int32_t)((m->N + vi.TN - 1) / vi.TN);
+    p.chunks_total = (int32_t)((m->K + vi.KC - 1) / vi.KC);
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    int64_t split = g_opt_split.load();
+    if (split <= 0) {
+        split = 1;
+        if (tiles < 512) split = (1024 + tiles - 1) / tiles;   // aim at ~4 workgroups per CU
+    }
+    const int64_t max_by_ws = (int64_t)(m->partial_bytes / ((size_t)m->M * (size_t)m->N * sizeof(float)));
+    if (split > max_by_ws) split = max_by_ws;
+    if (split > p.chunks_total) split = p.chunks_total;
+    if (split < 1) split = 1;
+    p.chunks_per_split = (int32_t)((p.chunks_total + split - 1) / split);
+    split = (p.chunks_total + p.chunks_per_split - 1) / p.chunks_per_split;   // drop empty splits
+    p.split_k = (int32_t)split;
+    p.workgroups = tiles * split;
+    return p;
+}
+
+}   // namespace
+
+extern "C" {
+
+const char *mmm_status_string(mmm_status st)
+{
+    switch (st) {
+    case MMM_OK: return "ok";
+    case MMM_ERR_INVALID_ARG: return "invalid argument";
+    case MMM_ERR_SHAPE: return "invalid shape";
+    case MMM_ERR_DTYPE: return "invalid element type or alignment";
+    case MMM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case MMM_ERR_MAPS_MISMATCH: return "maps not built or built for different inputs";
+    case MMM_ERR_DEVICE: return "device error";
+    }
+    return "unknown status";
+}
+
+mmm_status mmm_maps_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t block_width, size_t *bytes)
+{
+    if (bytes == nullptr) return MMM_ERR_INVALID_ARG;
+    if (!shape_ok(M, K, N, block_width)) return MMM_ERR_SHAPE;
+    *bytes = make_layout(M, K, N, block_width).total;
+    return MMM_OK;
+}
+
+mmm_status mmm_maps_init(void *dev_workspace, size_t workspace_bytes, int64_t M, int64_t K, int64_t N,
+                         int32_t block_width, mmm_maps **out)
+{
+    if (out == nullptr) return MMM_ERR_INVALID_ARG;
+    if (!shape_ok(M, K, N, block_width)) return MMM_ERR_SHAPE;
+    const Layout l = make_layout(M, K, N, block_width);
+    if (dev_workspace == nullptr || reinterpret_cast<uintptr_t>(dev_workspace) % kAlign != 0 ||
+        workspace_bytes < l.total)
+        return MMM_ERR_WORKSPACE;
+    mmm_maps *m = new (std::nothrow) mmm_maps();
+    if (m == nullptr) return MMM_ERR_INVALID_ARG;
+    m->M = M;
+    m->K = K;
+    m->N = N;
+    m->bw = block_width;
+    m->NB = N / block_width;
+    m->WA = (K + 63) / 64;
+    m->WB = (m->NB + 63) / 64;
+    m->MT = (M + MMM_COLANY_ROWS - 1) / MMM_COLANY_ROWS;
+    char *base = static_cast<char *>(dev_workspace);
+    m->a_bits = reinterpret_cast<uint64_t *>(base + l.a_bits);
+    m->a_colany = reinterpret_cast<uint64_t *>(base + l.a_colany);
+    m->b_bits = reinterpret_cast<uint64_t *>(base + l.b_bits);
+    m->bt_bits = reinterpret_cast<uint64_t *>(base + l.bt_bits);
+    m->stats = reinterpret_cast<uint64_t *>(base + l.stats);
+    m->partials = reinterpret_cast<float *>(base + l.partials);
+    m->partial_bytes = l.partial_bytes;
+    m->ws = dev_workspace;
+    m->ws_bytes = workspace_bytes;
+    m->a_built = m->b_built = false;
+    m->a_dtype = m->b_dtype = -1;
+    *out = m;
+    return MMM_OK;
+}
+
+void mmm_maps_release(mmm_maps *maps) { delete maps; }
+
+mmm_status mmm_build_maps(mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const mmm_mask_a *ma,
+                          const void *Y, int64_t ldy, const mmm_mask_b *mb, void *hip_stream)
+{
+    if (maps == nullptr || (X == nullptr && Y == nullptr)) return MMM_ERR_INVALID_ARG;
+    if (!dtype_ok(dt)) return MMM_ERR_DTYPE;
+    const size_t esz = elem_size(dt);
+    mmm_build_args a{};
+    a.dtype = dt;
+    if (X != nullptr) {
+        if (ma == nullptr) return MMM_ERR_INVALID_ARG;
+        if (ma->pred < MMM_PRED_NONZERO || ma->pred > MMM_PRED_ABS_GT) return MMM_ERR_INVALID_ARG;
+        if (ldx < maps->K) return MMM_ERR_SHAPE;
+        if (reinterpret_cast<uintptr_t>(X) % esz != 0) return MMM_ERR_DTYPE;
+        if (ma->keep_bits != nullptr && reinterpret_cast<uintptr_t>(ma->keep_bits) % 8 != 0) return MMM_ERR_INVALID_ARG;
+        a.X = X;
+        a.ldx = ldx;
+        a.pred = ma->pred;
+        a.threshold = ma->threshold;
+        a.keep_a = ma->keep_bits;
+    }
+    if (Y != nullptr) {
+        if (mb == nullptr) return MMM_ERR_INVALID_ARG;
+        if (mb->block_width != maps->bw) return MMM_ERR_SHAPE;
+        if (ldy < maps->N) return MMM_ERR_SHAPE;
+        if (reinterpret_cast<uintptr_t>(Y) % esz != 0) return MMM_ERR_DTYPE;
+        if ((mb->keep_rows != nullptr && reinterpret_cast<uintptr_t>(mb->keep_rows) % 8 != 0) ||
+            (mb->keep_blocks != nullptr && reinterpret_cast<uintptr_t>(mb->keep_blocks) % 8 != 0))
+            return MMM_ERR_INVALID_ARG;
+        a.Y = Y;
+        a.ldy = ldy;
+        a.keep_rows = mb->keep_rows;
+        a.keep_blocks = mb->keep_blocks;
+    }
+    if (mmm_launch_build(maps, a, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return MMM_ERR_DEVICE;
+    if (X != nullptr) {
+        maps->a_built = true;
+        maps->a_dtype = dt;
+    }
+    if (Y != nullptr) {
+        maps->b_built = true;
+        maps->b_dtype = dt;
+    }
+    return MMM_OK;
+}
+
+mmm_status mmm_maps_view(const mmm_maps *maps, const uint64_t **a_bits, int64_t *a_row_words,
+                         const uint64_t **b_bits, int64_t *b_row_words)
+{
+    if (maps == nullptr) return MMM_ERR_INVALID_ARG;
+    if (a_bits) *a_bits = maps->a_bits;
+    if (a_row_words) *a_row_words = maps->WA;
+    if (b_bits) *b_bits = maps->b_bits;
+    if (b_row_words) *b_row_words = maps->WB;
+    return MMM_OK;
+}
+
+mmm_status mmm_maps_view_derived(const mmm_maps *maps, const uint64_t **a_colany, const uint64_t **bt_bits,
+                                 int64_t *k_words)
+{
+    if (maps == nullptr) return MMM_ERR_INVALID_ARG;
+    if (a_colany) *a_colany = maps->a_colany;
+    if (bt_bits) *bt_bits = maps->bt_bits;
+    if (k_words) *k_words = maps->WA;
+    return MMM_OK;
+}
+
+mmm_status mmm_maps_stats(const mmm_maps *maps, uint64_t *nnz_a, uint64_t *occupied_blocks_b,
+                          uint64_t *useful_macs, void *hip_stream)
+{
+    if (maps == nullptr) return MMM_ERR_INVALID_ARG;
+    if (!maps->a_built || !maps->b_built) return MMM_ERR_MAPS_MISMATCH;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (mmm_launch_stats(maps, s) != hipSuccess) return MMM_ERR_DEVICE;
+    uint64_t host[4] = {0, 0, 0, 0};
+    if (hipMemcpyAsync(host, maps->stats, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess) return MMM_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return MMM_ERR_DEVICE;
+    if (nnz_a) *nnz_a = host[0];
+    if (occupied_blocks_b) *occupied_blocks_b = host[1];
+    if (useful_macs) *useful_macs = host[2];
+    return MMM_OK;
+}
+
+mmm_status mmm_matmul_plan(const mmm_maps *maps, mmm_dtype dt, int32_t *variant, int32_t *split_k, int64_t *workgroups)
+{
+    if (maps == nullptr) return MMM_ERR_INVALID_ARG;
+    if (!dtype_ok(dt)) return MMM_ERR_DTYPE;
+    const mmm_plan p = make_plan(maps, dt);
+    if (variant) *variant = p.variant;
+    if (split_k) *split_k = p.split_k;
+    if (workgroups) *workgroups = p.workgroups;
+    return MMM_OK;
+}
+
+mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const void *Y, int64_t ldy,
+                      float *C, int64_t ldc, int32_t accumulate, void *hip_stream)
+{
+    if (maps == nullptr || X == nullptr || Y == nullptr || C == nullptr) return MMM_ERR_INVALID_ARG;
+    if (!dtype_ok(dt)) return MMM_ERR_DTYPE;
+    if (ldx < maps->K || ldy < maps->N || ldc < maps->N) return MMM_ERR_SHAPE;
+    const size_t esz = elem_size(dt);
+    if (reinterpret_cast<uintptr_t>(X) % esz != 0 || reinterpret_cast<uintptr_t>(Y) % esz != 0 ||
+        reinterpret_cast<uintptr_t>(C) % sizeof(float) != 0)
+        return MMM_ERR_DTYPE;
+    if (!maps->a_built || !maps->b_built) return MMM_ERR_MAPS_MISMATCH;
+    if (maps->a_dtype != dt || maps->b_dtype != dt) return MMM_ERR_MAPS_MISMATCH;
+    const mmm_plan p = make_plan(maps, dt);
+    if (mmm_launch_matmul(maps, p, dt, X, ldx, Y, ldy, C, ldc, accumulate ? 1 : 0,
+                          static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return MMM_ERR_DEVICE;
+    return MMM_OK;
+}
+
+mmm_status mmm_set_option(const char *name, int64_t value)
+{
+    if (name == nullptr) return MMM_ERR_INVALID_ARG;
+    if (std::strcmp(name, "matmul_variant") == 0) {
+        if (value < -1 || value >= mmm_variant_count()) return MMM_ERR_INVALID_ARG;
+        g_opt_variant.store(value);
+        return MMM_OK;
+    }
+    if (std::strcmp(name, "split_k") == 0) {
+        if (value < 0 || value > 4096) return MMM_ERR_INVALID_ARG;
+        g_opt_split.store(value);
+        return MMM_OK;
+    }
+    return MMM_ERR_INVALID_ARG;
+}
+
+int32_t mmm_matmul_variant_count(void) { return mmm_variant_count(); }
+
+const char *mmm_matmul_variant_name(int32_t i)
+{
+    if (i < 0 || i >= mmm_variant_count()) return nullptr;
+    return mmm_variant(i).name;
+}
+
+}   // extern "C"

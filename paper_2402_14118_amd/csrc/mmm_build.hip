@@ -1,0 +1,244 @@
+// Map builder: evaluates the masks M and N on the device and writes the
+// sparsity maps (paper, section 3 "Preprocessing": a single sequential, aligned
+// pass; one bit per vector of B, 1 = some non-zero value; the non-zero positions
+// of A per row).  Everything here is integer work on float bit patterns, bound
+// by HBM bandwidth.
+//
+// One launch covers both matrices: the first n_a workgroups scan X, the rest
+// scan Y.  Every output word has exactly one producer, so there are no atomics
+// and nothing needs clearing beforehand.
+#include "mmm_internal.h"
+
+namespace {
+
+constexpr int BUILD_THREADS = 256;
+constexpr int A_ROWS_PER_WAVE = MMM_COLANY_ROWS / 4;   // 8
+constexpr int B_ROWS_PER_WAVE = MMM_BT_PIECE / 4;      // 4
+
+struct BuildParams {
+    const void *X;
+    int64_t ldx;
+    const uint64_t *keep_a;
+    uint64_t *a_bits;
+    uint64_t *a_colany;
+    const void *Y;
+    int64_t ldy;
+    const uint64_t *keep_rows;
+    const uint64_t *keep_blocks;
+    uint64_t *b_bits;
+    uint16_t *bt16;
+    int64_t M, K, N, NB, WA, WB;
+    uint32_t thr_bits;
+    int32_t pred;
+    uint32_t n_a;   // workgroups that scan X
+};
+
+template <typename T> __device__ __forceinline__ uint32_t f32_bits(T v);
+template <> __device__ __forceinline__ uint32_t f32_bits<float>(float v) { return __float_as_uint(v); }
+template <> __device__ __forceinline__ uint32_t f32_bits<uint16_t>(uint16_t v) { return (uint32_t)v << 16; }
+
+// Order-preserving key of a non-NaN float with both zeros mapped to +0.
+__device__ __forceinline__ uint32_t order_key(uint32_t u)
+{
+    if ((u & 0x7fffffffu) == 0) u = 0;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ bool is_nan_bits(uint32_t u) { return (u & 0x7fffffffu) > 0x7f800000u; }
+
+// Element predicate of M, decided on the bit pattern so that no denormal mode
+// of the float pipeline can change a map bit.  Includes the non-zero test.
+__device__ __forceinline__ bool keep_element(uint32_t u, int32_t pred, uint32_t t)
+{
+    const bool nz = (u & 0x7fffffffu) != 0;
+    if (pred == MMM_PRED_NONZERO) return nz;
+    if (is_nan_bits(u) || is_nan_bits(t)) return false;
+    if (pred == MMM_PRED_GT) return nz && order_key(u) > order_key(t);
+    // |x| > t
+    const uint32_t at = t & 0x7fffffffu;
+    if ((t & 0x80000000u) && at != 0) return nz;   // negative threshold: every |x| exceeds it
+    return nz && (u & 0x7fffffffu) > at;
+}
+
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
+
+// ---- A side: one workgroup = 32 rows x 64 columns --------------------------------------------
+template <typename T>
+__device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lane, int wave, uint64_t *red)
+{
+    const int64_t t = b / p.WA, w = b % p.WA;
+    const int64_t k = w * 64 + lane;
+    const int64_t rbase = t * MMM_COLANY_ROWS + wave * A_ROWS_PER_WAVE;
+    const T *X = static_cast<const T *>(p.X);
+    uint32_t u[A_ROWS_PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
+        const int64_t r = rbase + j;
+        u[j] = 0;
+        if (r < p.M && k < p.K) u[j] = f32_bits<T>(X[r * p.ldx + k]);
+    }
+    uint64_t colany = 0, mine = 0;
+#pragma unroll
+    for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
+        const int64_t r = rbase + j;
+        uint64_t m = ballot64(keep_element(u[j], p.pred, p.thr_bits));   // lanes past K or M hold +0
+        if (p.keep_a != nullptr && r < p.M) m &= p.keep_a[r * p.WA + w];
+        colany |= m;
+        if (lane == j) mine = m;
+    }
+    if (lane < A_ROWS_PER_WAVE && rbase + lane < p.M) p.a_bits[(rbase + lane) * p.WA + w] = mine;
+    if (lane == 0) red[wave] = colany;
+    __syncthreads();
+    if (threadIdx.x == 0) p.a_colany[t * p.WA + w] = red[0] | red[1] | red[2] | red[3];
+}
+
+// ---- B side: one workgroup = 16 rows (values of k) x 64 blocks -------------------------------
+template <typename T, int BW>
+__device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int lane, int wave, uint32_t *pieces)
+{
+    constexpr int BPL = 64 / BW;   // blocks covered by one 64-lane load
+    const int64_t piece = bb / p.WB, w = bb % p.WB;
+    const int64_t kbase = piece * MMM_BT_PIECE + wave * B_ROWS_PER_WAVE;
+    const T *Y = static_cast<const T *>(p.Y);
+    const int64_t nb_left = p.NB - w * 64;
+    const uint64_t valid = nb_left >= 64 ? ~0ull : ((1ull << nb_left) - 1ull);
+    uint32_t piece_bits = 0;
+    for (int r = 0; r < B_ROWS_PER_WAVE; ++r) {
+        const int64_t k = kbase + r;
+        uint64_t word = 0;
+        if (k < p.K) {
+            uint64_t kept = valid;
+            if (p.keep_rows != nullptr && !((p.keep_rows[k >> 6] >> (k & 63)) & 1ull)) kept = 0;
+            if (p.keep_blocks != nullptr) kept &= p.keep_blocks[k * p.WB + w];
+            if (kept != 0) {
+                const T *row = Y + k * p.ldy + w * 64 * BW;
+                uint32_t u[BW];
+#pragma unroll
+                for (int j = 0; j < BW; ++j) {
+                    const int blk = j * BPL + lane / BW;   // block (inside this word) of this lane's element
+                    u[j] = 0;
+                    if ((kept >> blk) & 1ull) u[j] = f32_bits<T>(row[j * 64 + lane]);
+                }
+                uint64_t mine = 0;
+#pragma unroll
+                for (int j = 0; j < BW; ++j) {
+                    const uint64_t m = ballot64((u[j] & 0x7fffffffu) != 0);
+                    if (lane / BPL == j) mine = m;   // lane L collects the load that holds block L
+                }
+                const uint64_t bwmask = BW == 32 ? 0xffffffffull : ((1ull << BW) - 1ull);
+                word = ballot64(((mine >> ((lane % BPL) * BW)) & bwmask) != 0);
+            }
+            if (lane == 0) p.b_bits[k * p.WB + w] = word;
+        }
+        piece_bits |= (uint32_t)((word >> lane) & 1ull) << (wave * B_ROWS_PER_WAVE + r);
+    }
+    pieces[wave * 64 + lane] = piece_bits;
+    __syncthreads();
+    if (wave == 0) {
+        const uint32_t v = pieces[lane] | pieces[64 + lane] | pieces[128 + lane] | pieces[192 + lane];
+        const int64_t blk = w * 64 + lane;
+        if (blk < p.NB) p.bt16[blk * (p.WA * 4) + piece] = (uint16_t)v;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(BUILD_THREADS) void mmm_build_kernel(const BuildParams p)
+{
+    __shared__ uint64_t red[4];
+    __shared__ uint32_t pieces[4 * 64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t b = blockIdx.x;
+    if (b < p.n_a) {
+        scan_a<T>(p, b, lane, wave, red);
+    } else {
+        const int64_t bw = p.N / p.NB;
+        if (bw == 8)
+            scan_b<T, 8>(p, b - p.n_a, lane, wave, pieces);
+        else if (bw == 16)
+            scan_b<T, 16>(p, b - p.n_a, lane, wave, pieces);
+        else
+            scan_b<T, 32>(p, b - p.n_a, lane, wave, pieces);
+    }
+}
+
+// ---- statistics (off the hot path) -----------------------------------------------------------
+__global__ void mmm_stats_clear_kernel(uint64_t *stats)
+{
+    if (threadIdx.x < 4) stats[threadIdx.x] = 0;
+}
+
+// One workgroup per 64 values of k: lane kb of every wave counts column k of A
+// over a slice of rows and row k of B over its words.
+__global__ __launch_bounds__(256) void mmm_stats_kernel(const uint64_t *a_bits, const uint64_t *b_bits,
+                                                        int64_t M, int64_t K, int64_t WA, int64_t WB,
+                                                        int64_t bw, uint64_t *stats)
+{
+    __shared__ uint32_t col[4 * 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t w = blockIdx.x;
+    uint32_t cnt = 0;
+    for (int64_t r = wave; r < M; r += 4) cnt += (uint32_t)((a_bits[r * WA + w] >> lane) & 1ull);
+    col[wave * 64 + lane] = cnt;
+    __syncthreads();
+    if (wave == 0) {
+        const uint64_t colcount = (uint64_t)col[lane] + col[64 + lane] + col[128 + lane] + col[192 + lane];
+        const int64_t k = w * 64 + lane;
+        uint64_t rowcount = 0;
+        if (k < K)
+            for (int64_t j = 0; j < WB; ++j) rowcount += (uint64_t)__popcll(b_bits[k * WB + j]);
+        uint64_t v[3] = {colcount, rowcount, colcount * rowcount * (uint64_t)bw};
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+            uint64_t x = v[q];
+            for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
+            if (lane == 0 && x != 0) atomicAdd((unsigned long long *)&stats[q], (unsigned long long)x);
+        }
+    }
+}
+
+}   // namespace
+
+hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStream_t s)
+{
+    BuildParams p{};
+    p.X = a.X;
+    p.ldx = a.ldx;
+    p.keep_a = a.keep_a;
+    p.a_bits = m->a_bits;
+    p.a_colany = m->a_colany;
+    p.Y = a.Y;
+    p.ldy = a.ldy;
+    p.keep_rows = a.keep_rows;
+    p.keep_blocks = a.keep_blocks;
+    p.b_bits = m->b_bits;
+    p.bt16 = reinterpret_cast<uint16_t *>(m->bt_bits);
+    p.M = m->M;
+    p.K = m->K;
+    p.N = m->N;
+    p.NB = m->NB;
+    p.WA = m->WA;
+    p.WB = m->WB;
+    p.pred = a.pred;
+    union { float f; uint32_t u; } cv;
+    cv.f = a.threshold;
+    p.thr_bits = cv.u;
+    const int64_t n_a = a.X ? m->MT * m->WA : 0;
+    const int64_t n_b = a.Y ? (m->WA * (64 / MMM_BT_PIECE)) * m->WB : 0;
+    if (n_a + n_b <= 0 || n_a + n_b > 0x7fffffffLL) return hipErrorInvalidValue;
+    p.n_a = (uint32_t)n_a;
+    const dim3 grid((uint32_t)(n_a + n_b)), block(BUILD_THREADS);
+    if (a.dtype == MMM_BF16)
+        hipLaunchKernelGGL(mmm_build_kernel<uint16_t>, grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL(mmm_build_kernel<float>, grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t mmm_launch_stats(const mmm_maps *m, hipStream_t s)
+{
+    hipLaunchKernelGGL(mmm_stats_clear_kernel, dim3(1), dim3(64), 0, s, m->stats);
+    hipLaunchKernelGGL(mmm_stats_kernel, dim3((uint32_t)m->WA), dim3(256), 0, s, m->a_bits, m->b_bits, m->M,
+                       m->K, m->WA, m->WB, (int64_t)m->bw, m->stats);
+    return hipGetLastError();
+}

@@ -1,0 +1,73 @@
+// Internal declarations shared by the host API and the kernel launchers.
+// Not part of the public ABI (that is include/mmm.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "mmm.h"
+
+// Rows of A summarised by one column-any word.
+constexpr int MMM_COLANY_ROWS = 32;
+// Rows of B (values of k) one workgroup of the B-side map builder covers; the
+// transposed map is written in pieces of this many bits.
+constexpr int MMM_BT_PIECE = 16;
+
+struct mmm_maps {
+    int64_t M, K, N;
+    int32_t bw;
+    int64_t NB;        // N / bw
+    int64_t WA;        // ceil(K/64): words per row of a_bits, a_colany and bt_bits
+    int64_t WB;        // ceil(NB/64): words per row of b_bits
+    int64_t MT;        // ceil(M/32): rows of a_colany
+    // device pointers into the caller's workspace
+    uint64_t *a_bits;
+    uint64_t *a_colany;
+    uint64_t *b_bits;
+    uint64_t *bt_bits;
+    uint64_t *stats;   // 4 words
+    float *partials;   // split-K partial sums
+    size_t partial_bytes;
+    void *ws;
+    size_t ws_bytes;
+    // state
+    bool a_built, b_built;
+    int32_t a_dtype, b_dtype;
+};
+
+struct mmm_build_args {
+    // A side (X == nullptr: skip)
+    const void *X;
+    int64_t ldx;
+    int32_t pred;
+    float threshold;
+    const uint64_t *keep_a;
+    // B side (Y == nullptr: skip)
+    const void *Y;
+    int64_t ldy;
+    const uint64_t *keep_rows;
+    const uint64_t *keep_blocks;
+    int32_t dtype;
+};
+
+struct mmm_plan {
+    int32_t variant;
+    int32_t split_k;
+    int32_t tiles_m, tiles_n;
+    int32_t chunks_total;      // ceil(K / KC)
+    int32_t chunks_per_split;
+    int64_t workgroups;
+};
+
+struct mmm_variant_info {
+    const char *name;
+    int32_t TM, TN, KC, threads;
+};
+
+hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStream_t s);
+hipError_t mmm_launch_stats(const mmm_maps *m, hipStream_t s);
+int32_t mmm_variant_count();
+const mmm_variant_info &mmm_variant(int32_t i);
+hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &p, int32_t dtype, const void *X, int64_t ldx,
+                             const void *Y, int64_t ldy, float *C, int64_t ldc, int32_t accumulate,
+                             hipStream_t s);

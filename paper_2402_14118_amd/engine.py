@@ -1,0 +1,77 @@
+"""Convenience holder for one MMM problem on the current CUDA/HIP device.
+
+Owns the workspace tensor and the maps handle and forwards to the C ABI; it does
+no arithmetic of its own.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import binding as B
+
+
+class MaskedMatmul:
+    def __init__(self, M: int, K: int, N: int, block_width: int, dtype: int = B.MMM_F32, device="cuda:0"):
+        self.M, self.K, self.N, self.bw, self.dtype = M, K, N, block_width, dtype
+        self.device = torch.device(device)
+        nbytes = B.mmm_maps_workspace_bytes(M, K, N, block_width)
+        # torch's caching allocator hands out >= 512-byte aligned blocks
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.maps = B.mmm_maps_init(self.workspace, nbytes, M, K, N, block_width)
+        self._keep = []
+
+    def close(self) -> None:
+        if self.maps is not None:
+            B.mmm_maps_release(self.maps)
+            self.maps = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def build_maps(self, X: Optional[torch.Tensor], Y: Optional[torch.Tensor], pred: int = B.MMM_PRED_NONZERO,
+                   threshold: float = 0.0, keep_a: Optional[torch.Tensor] = None,
+                   keep_rows: Optional[torch.Tensor] = None, keep_blocks: Optional[torch.Tensor] = None,
+                   stream=None) -> None:
+        ma = mb = None
+        if X is not None:
+            ma = B.MaskA(pred, threshold, B._ptr(keep_a))
+        if Y is not None:
+            mb = B.MaskB(self.bw, B._ptr(keep_rows), B._ptr(keep_blocks))
+        B.mmm_build_maps(self.maps, self.dtype, X, X.stride(0) if X is not None else 0, ma,
+                         Y, Y.stride(0) if Y is not None else 0, mb, stream)
+
+    def matmul(self, X: torch.Tensor, Y: torch.Tensor, C: torch.Tensor, accumulate: bool = False, stream=None) -> None:
+        B.mmm_matmul(self.maps, self.dtype, X, X.stride(0), Y, Y.stride(0), C, C.stride(0), int(accumulate), stream)
+
+    def stats(self, stream=None):
+        return B.mmm_maps_stats(self.maps, stream)
+
+    def plan(self):
+        return B.mmm_matmul_plan(self.maps, self.dtype)
+
+    def _bits_tensor(self, addr: int, rows: int, words: int) -> torch.Tensor:
+        off = addr - self.workspace.data_ptr()
+        assert 0 <= off and off + rows * words * 8 <= self.workspace.numel()
+        return self.workspace[off: off + rows * words * 8].view(torch.int64).view(rows, words)
+
+    def a_bits(self) -> torch.Tensor:
+        a, aw, _, _ = B.mmm_maps_view(self.maps)
+        return self._bits_tensor(a, self.M, aw)
+
+    def b_bits(self) -> torch.Tensor:
+        _, _, b, bw = B.mmm_maps_view(self.maps)
+        return self._bits_tensor(b, self.K, bw)
+
+    def a_colany(self) -> torch.Tensor:
+        a, _, kw = B.mmm_maps_view_derived(self.maps)
+        return self._bits_tensor(a, (self.M + 31) // 32, kw)
+
+    def bt_bits(self) -> torch.Tensor:
+        _, b, kw = B.mmm_maps_view_derived(self.maps)
+        return self._bits_tensor(b, self.N // self.bw, kw)

@@ -1,0 +1,253 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Maps must match bit for bit; C must satisfy
+|C - C_ref| <= 1e-5 * (|A| x |B|) + 1e-6 in fp32 (1e-2 for bf16 inputs), and be
+bit-exact where every product and partial sum is an exact integer."""
+import numpy as np
+import pytest
+import torch
+
+import mmm_synth as synth
+import oracle
+import paper_2402_14118_amd as mm
+from hip_harness import HipRun, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _auto_options():
+    mm.mmm_set_option("matmul_variant", -1)
+    mm.mmm_set_option("split_k", 0)
+    yield
+    mm.mmm_set_option("matmul_variant", -1)
+    mm.mmm_set_option("split_k", 0)
+
+
+def derived_from_bits(ab, bb, M, K, NB):
+    """Column-any words per 32-row tile and the transposed B map, from the oracle's bitmaps."""
+    a = synth.unpack_bits(ab, K)
+    pad = (-M) % 32
+    a = np.concatenate([a, np.zeros((pad, K), bool)]) if pad else a
+    colany = synth.pack_bits(a.reshape(-1, 32, K).any(axis=1))
+    bt = synth.pack_bits(synth.unpack_bits(bb, NB).T)
+    return colany, bt
+
+
+def check_workload(w, what, exact=False, **ld):
+    print(f"case {what}: M={w.M} K={w.K} N={w.N} bw={w.bw} dtype={w.dtype}", flush=True)
+    ab, bb, C_ref, mag = oracle.run_workload(w)
+    run = HipRun(w, **ld)
+    a_hip, b_hip, C = run.run()
+    np.testing.assert_array_equal(a_hip, ab, err_msg=f"{what}: a_bits")
+    np.testing.assert_array_equal(b_hip, bb, err_msg=f"{what}: b_bits")
+    colany, bt = run.derived_host()
+    exp_colany, exp_bt = derived_from_bits(ab, bb, w.M, w.K, w.N // w.bw)
+    np.testing.assert_array_equal(colany, exp_colany, err_msg=f"{what}: a_colany")
+    np.testing.assert_array_equal(bt, exp_bt, err_msg=f"{what}: bt_bits")
+    assert run.eng.stats() == oracle.counts(ab, bb, w.M, w.K, w.N, w.bw), what
+    if exact:
+        np.testing.assert_array_equal(C, C_ref, err_msg=what)
+    else:
+        assert_close(C, C_ref, mag, w.dtype, what)
+    assert not np.isnan(run.Cbuf[:, : w.N].cpu().numpy()).any()
+    return run, (ab, bb, C_ref, mag, C)
+
+
+# ---- small sizes, element by element: several tiles and ragged tails ------------------------
+SHAPES = [
+    (1, 1, 8, 8), (1, 1, 16, 16), (1, 1, 32, 32),
+    (5, 7, 24, 8),              # N not a multiple of 16 with bw 8: half a column group
+    (33, 65, 48, 16),           # one row / one k past a tile edge
+    (70, 200, 272, 16),         # ragged in every dimension
+    (100, 130, 96, 32),
+    (64, 128, 256, 16),         # exactly one tile of the default variant
+    (129, 257, 520, 8),
+    (200, 1000, 320, 32),
+]
+
+
+@pytest.mark.parametrize("M,K,N,bw", SHAPES)
+def test_small_shapes_exact_integers(M, K, N, bw):
+    w = synth.random_masked(M, K, N, bw, 0.3, 0.4, 500 + M + K, dist="smallint", p_rows=0.8)
+    check_workload(w, f"int {M}x{K}x{N} bw{bw}", exact=True)
+
+
+@pytest.mark.parametrize("M,K,N,bw", SHAPES[3:])
+def test_small_shapes_float(M, K, N, bw):
+    w = synth.random_masked(M, K, N, bw, 0.25, 0.3, 900 + N, dist="normal")
+    check_workload(w, f"f32 {M}x{K}x{N} bw{bw}")
+
+
+@pytest.mark.parametrize("variant", range(7))
+@pytest.mark.parametrize("split", [1, 3])
+def test_every_variant_and_split(variant, split):
+    assert mm.mmm_matmul_variant_count() == 7
+    mm.mmm_set_option("matmul_variant", variant)
+    mm.mmm_set_option("split_k", split)
+    w = synth.random_masked(150, 700, 400, 16, 0.3, 0.3, 77, dist="smallint")
+    run, _ = check_workload(w, f"variant {variant} split {split}", exact=True)
+    v, s, _ = run.eng.plan()
+    assert v == variant and s == split
+
+
+def test_padded_leading_dimensions_and_unaligned_rows():
+    w = synth.random_masked(70, 203, 80, 16, 0.3, 0.5, 31, dist="smallint")
+    check_workload(w, "ld padded", exact=True, ldx=209, ldy=83, ldc=91)
+
+
+def test_predicates_and_special_values():
+    rng = np.random.default_rng(12)
+    M, K, N, bw = 40, 96, 64, 16
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    X[0, :8] = [0.0, -0.0, 1e-45, -1e-40, 3e-39, -2.0, 0.5, 1.0]     # zeros and denormals
+    X[1, 5] = np.nan                                                   # NaN is dropped by > and |.| >
+    Y = rng.standard_normal((K, N)).astype(np.float32)
+    Y[3, 16:32] = 0.0
+    Y[3, 20] = -0.0                                                    # all-zero block: unoccupied
+    Y[4, 32:48] = 0.0
+    Y[4, 40] = 1e-45                                                   # denormal occupies its block
+    for pred, thr in [(synth.PRED_GT, 0.0), (synth.PRED_GT, -0.5), (synth.PRED_ABS_GT, 0.7),
+                      (synth.PRED_ABS_GT, -1.0), (synth.PRED_GT, 1e-40)]:
+        w = synth.Workload("pred", M, K, N, bw, synth.DT_F32, X, Y, pred=pred, threshold=thr)
+        ab = oracle.a_bits(X, pred, thr)
+        bb = oracle.b_bits(Y, bw)
+        run = HipRun(w)
+        run.build()
+        a_hip, b_hip = run.maps_host()
+        np.testing.assert_array_equal(a_hip, ab, err_msg=f"pred {pred} thr {thr}")
+        np.testing.assert_array_equal(b_hip, bb)
+    # NONZERO keeps the NaN: checked on maps only (the product would be NaN on both sides)
+    ab = oracle.a_bits(X)
+    w = synth.Workload("nz", M, K, N, bw, synth.DT_F32, X, Y)
+    run = HipRun(w)
+    run.build()
+    np.testing.assert_array_equal(run.maps_host()[0], ab)
+
+
+def test_masked_positions_may_hold_anything():
+    """Masked-out X elements and switched-off Y blocks never reach the arithmetic."""
+    w = synth.random_masked(64, 256, 128, 16, 0.3, 0.3, 5, dist="smallint")
+    ab, bb, C_ref, _ = oracle.run_workload(w)
+    keepa = synth.unpack_bits(w.keep_a, w.K)
+    keepb = np.repeat(synth.unpack_bits(w.keep_blocks, w.N // w.bw), w.bw, axis=1)
+    w.X = np.where(keepa, w.X, np.float32(np.nan))
+    w.Y = np.where(keepb, w.Y, np.float32(np.inf))
+    a_hip, b_hip, C = HipRun(w).run()
+    np.testing.assert_array_equal(a_hip, ab)
+    np.testing.assert_array_equal(b_hip, bb)
+    np.testing.assert_array_equal(C, C_ref)
+
+
+def test_identity_zero_and_full_masks():
+    n, bw = 96, 16
+    rng = np.random.default_rng(2)
+    Y = rng.standard_normal((n, n)).astype(np.float32)
+    eye = np.eye(n, dtype=np.float32)
+    kb = synth.pack_bits(rng.random((n, n // bw)) < 0.5)
+    w = synth.Workload("I*Y", n, n, n, bw, synth.DT_F32, eye, Y, keep_blocks=kb)
+    _, _, C = HipRun(w).run()
+    np.testing.assert_array_equal(C, np.where(np.repeat(synth.unpack_bits(kb, n // bw), bw, axis=1), Y, 0))
+    ka = synth.pack_bits(rng.random((n, n)) < 0.3)
+    w = synth.Workload("X*I", n, n, n, bw, synth.DT_F32, Y, eye, keep_a=ka)
+    _, _, C = HipRun(w).run()
+    np.testing.assert_array_equal(C, np.where(synth.unpack_bits(ka, n), Y, 0))
+    for pa, pb in [(0.0, 0.5), (0.5, 0.0)]:
+        w = synth.random_masked(50, 130, 64, 16, pa, pb, 8)
+        run, (_, _, _, _, C) = check_workload(w, f"zero mask {pa},{pb}", exact=True)
+        assert not C.any() and not np.signbit(C).any()
+        assert run.eng.stats()[2] == 0
+    w = synth.random_masked(48, 100, 64, 16, 1.0, 1.0, 9, dist="normal")     # nothing masked: plain GEMM
+    _, (_, _, _, mag, C) = check_workload(w, "all keep")
+    ref = w.X.astype(np.float64) @ w.Y.astype(np.float64)
+    assert np.all(np.abs(C - ref) <= 1e-5 * mag + 1e-6)
+
+
+def test_accumulate_and_cached_b_map():
+    w = synth.random_masked(90, 300, 160, 16, 0.3, 0.3, 21, dist="smallint")
+    ab, bb, C_ref, _ = oracle.run_workload(w)
+    run = HipRun(w)
+    run.build()
+    run.matmul()
+    run.matmul(accumulate=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(run.C.cpu().numpy(), 2 * C_ref)
+    # new activations against the cached B map: only the A side is rebuilt
+    w2 = synth.random_masked(90, 300, 160, 16, 0.5, 0.3, 22, dist="smallint")
+    w2.Y, w2.keep_blocks = w.Y, w.keep_blocks
+    ab2, bb2, C2_ref, _ = oracle.run_workload(w2)
+    run.X.copy_(torch.from_numpy(w2.X))
+    run.keep_a.copy_(torch.from_numpy(w2.keep_a.view(np.int64)))
+    run.build(a=True, b=False)
+    run.matmul()
+    a_hip, b_hip = run.maps_host()
+    np.testing.assert_array_equal(a_hip, ab2)
+    np.testing.assert_array_equal(b_hip, bb)
+    np.testing.assert_array_equal(run.C.cpu().numpy(), C2_ref)
+
+
+def test_run_to_run_bitwise_reproducible():
+    w = synth.config(2, scale=4)
+    run = HipRun(w)
+    _, _, C1 = run.run()
+    run.Cbuf.fill_(float("nan"))
+    _, _, C2 = run.run()
+    np.testing.assert_array_equal(C1, C2)
+    mm.mmm_set_option("split_k", 4)
+    _, _, C3 = run.run()
+    _, _, C4 = run.run()
+    np.testing.assert_array_equal(C3, C4)
+
+
+def test_bf16_small():
+    w = synth.random_masked(32, 520, 96, 16, 0.3, 0.3, 17, dist="normal", dtype=synth.DT_BF16)
+    check_workload(w, "bf16 small")
+    w = synth.random_masked(45, 260, 64, 8, 0.3, 0.3, 18, dist="smallint", dtype=synth.DT_BF16)
+    check_workload(w, "bf16 int", exact=True)
+
+
+# ---- the benchmark configurations at full size ------------------------------------------------
+def test_config1_full():
+    check_workload(synth.config(1), "config 1")
+
+
+def test_config2_full():
+    run, _ = check_workload(synth.config(2), "config 2")
+    print("plan", run.eng.plan())
+
+
+def test_config5_full_bf16_decode():
+    run, _ = check_workload(synth.config(5), "config 5")
+    print("plan", run.eng.plan())
+
+
+def sampled_check(w, what, n_rows=48, n_elems=64):
+    """Full-size run in the benchmark's launch configuration, compared on sampled
+    rows (whole rows from the oracle) and sampled single elements."""
+    print(f"case {what}: M={w.M} K={w.K} N={w.N} bw={w.bw}", flush=True)
+    ab = oracle.a_bits(w.X, w.pred, w.threshold, w.keep_a)
+    bb = oracle.b_bits(w.Y, w.bw, w.keep_rows, w.keep_blocks)
+    run = HipRun(w)
+    a_hip, b_hip, C = run.run()
+    np.testing.assert_array_equal(a_hip, ab, err_msg=what)
+    np.testing.assert_array_equal(b_hip, bb, err_msg=what)
+    assert run.eng.stats() == oracle.counts(ab, bb, w.M, w.K, w.N, w.bw)
+    rng = np.random.default_rng(99)
+    rows = np.unique(np.concatenate([[0, w.M - 1], rng.integers(0, w.M, n_rows)]))
+    for r in rows:
+        Cr, mag = oracle.mmm(w.X, w.Y, ab, bb, w.bw, rows=(int(r), int(r) + 1))
+        assert_close(C[r:r + 1], Cr[r:r + 1], mag[r:r + 1], w.dtype, f"{what} row {r}")
+    for _ in range(n_elems):
+        i, j = int(rng.integers(0, w.M)), int(rng.integers(0, w.N))
+        c, m = oracle.mmm_element(w.X, w.Y, ab, bb, w.bw, i, j)
+        assert abs(float(C[i, j]) - c) <= 1e-5 * m + 1e-6, (what, i, j)
+    assert np.isfinite(C).all()
+    print("plan", run.eng.plan(), flush=True)
+
+
+@pytest.mark.parametrize("ip", [0, 3, 4])
+def test_config3_full_sampled(ip):
+    sampled_check(synth.config(3, ip), f"config 3 p={synth.SWEEP_P[ip]}")
+
+
+def test_config4_full_sampled():
+    sampled_check(synth.config(4), "config 4", n_rows=24)
