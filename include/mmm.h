@@ -174,6 +174,10 @@ mmm_status mmm_matmul_plan(const mmm_maps *maps, mmm_dtype dt, int32_t *variant,
 
 const char *mmm_status_string(mmm_status st);
 
+/* Text describing the HIP failure behind the most recent MMM_ERR_DEVICE returned
+ * on the calling thread ("" if none).  The pointer stays valid for the thread. */
+const char *mmm_last_device_error(void);
+
 #ifdef __cplusplus
 }
 #endif

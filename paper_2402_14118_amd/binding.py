@@ -10,6 +10,12 @@ import ctypes
 import os
 from typing import Optional
 
+# PyTorch ships its own HIP runtime (same soname as the system one).  Device
+# pointers and streams handed to the library come from PyTorch, so its runtime
+# must be the one already loaded when libmmm_hip.so is opened; loading ours first
+# leaves the process with a runtime that reports no device.
+import torch  # noqa: F401  (must precede ctypes.CDLL below)
+
 PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG, "libmmm_hip.so")
 
@@ -21,7 +27,7 @@ MMM_PRED_NONZERO, MMM_PRED_GT, MMM_PRED_ABS_GT = 0, 1, 2
 EXPORTS = [
     "mmm_maps_workspace_bytes", "mmm_maps_init", "mmm_maps_release", "mmm_build_maps", "mmm_maps_view",
     "mmm_maps_view_derived", "mmm_maps_stats", "mmm_matmul", "mmm_set_option", "mmm_matmul_variant_count",
-    "mmm_matmul_variant_name", "mmm_matmul_plan", "mmm_status_string",
+    "mmm_matmul_variant_name", "mmm_matmul_plan", "mmm_status_string", "mmm_last_device_error",
 ]
 
 
@@ -36,7 +42,8 @@ class MaskB(ctypes.Structure):
 class MmmError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {status_string(status)} (status {status})")
+        detail = f" [{mmm_last_device_error()}]" if status == MMM_ERR_DEVICE else ""
+        super().__init__(f"{where}: {status_string(status)} (status {status}){detail}")
 
 
 def _load() -> ctypes.CDLL:
@@ -63,6 +70,7 @@ def _load() -> ctypes.CDLL:
     lib.mmm_matmul_plan.argtypes = [vp, i32, c.POINTER(i32), c.POINTER(i32), c.POINTER(i64)]
     lib.mmm_status_string.argtypes = [i32]
     lib.mmm_status_string.restype = c.c_char_p
+    lib.mmm_last_device_error.restype = c.c_char_p
     return lib
 
 
@@ -71,6 +79,10 @@ lib = _load()
 
 def status_string(st: int) -> str:
     return lib.mmm_status_string(int(st)).decode()
+
+
+def mmm_last_device_error() -> str:
+    return lib.mmm_last_device_error().decode()
 
 
 def _check(st: int, where: str) -> None:

@@ -2,6 +2,7 @@
 // layout, launch planning.  All checks run before any device call, so they can
 // be exercised on a machine without a GPU.
 #include <atomic>
+#include <cstdio>
 #include <cstring>
 #include <new>
 
@@ -11,6 +12,13 @@ namespace {
 
 constexpr size_t kAlign = 256;
 constexpr size_t kPartialCap = (size_t)64 << 20;   // split-K partial sums: at most 64 MiB
+
+thread_local char g_detail[160] = "";
+
+void note_device_error(const char *where, hipError_t e)
+{
+    std::snprintf(g_detail, sizeof(g_detail), "%s: %s (%d)", where, hipGetErrorName(e), (int)e);
+}
 
 std::atomic<int64_t> g_opt_variant{-1};
 std::atomic<int64_t> g_opt_split{0};
@@ -191,7 +199,10 @@ mmm_status mmm_build_maps(mmm_maps *maps, mmm_dtype dt, const void *X, int64_t l
         a.keep_rows = mb->keep_rows;
         a.keep_blocks = mb->keep_blocks;
     }
-    if (mmm_launch_build(maps, a, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return MMM_ERR_DEVICE;
+    if (hipError_t e = mmm_launch_build(maps, a, static_cast<hipStream_t>(hip_stream)); e != hipSuccess) {
+        note_device_error("map builder launch", e);
+        return MMM_ERR_DEVICE;
+    }
     if (X != nullptr) {
         maps->a_built = true;
         maps->a_dtype = dt;
@@ -230,10 +241,14 @@ mmm_status mmm_maps_stats(const mmm_maps *maps, uint64_t *nnz_a, uint64_t *occup
     if (maps == nullptr) return MMM_ERR_INVALID_ARG;
     if (!maps->a_built || !maps->b_built) return MMM_ERR_MAPS_MISMATCH;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if (mmm_launch_stats(maps, s) != hipSuccess) return MMM_ERR_DEVICE;
+    hipError_t e = mmm_launch_stats(maps, s);
     uint64_t host[4] = {0, 0, 0, 0};
-    if (hipMemcpyAsync(host, maps->stats, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess) return MMM_ERR_DEVICE;
-    if (hipStreamSynchronize(s) != hipSuccess) return MMM_ERR_DEVICE;
+    if (e == hipSuccess) e = hipMemcpyAsync(host, maps->stats, sizeof(host), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+        note_device_error("statistics", e);
+        return MMM_ERR_DEVICE;
+    }
     if (nnz_a) *nnz_a = host[0];
     if (occupied_blocks_b) *occupied_blocks_b = host[1];
     if (useful_macs) *useful_macs = host[2];
@@ -264,9 +279,12 @@ mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t
     if (!maps->a_built || !maps->b_built) return MMM_ERR_MAPS_MISMATCH;
     if (maps->a_dtype != dt || maps->b_dtype != dt) return MMM_ERR_MAPS_MISMATCH;
     const mmm_plan p = make_plan(maps, dt);
-    if (mmm_launch_matmul(maps, p, dt, X, ldx, Y, ldy, C, ldc, accumulate ? 1 : 0,
-                          static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    if (hipError_t e = mmm_launch_matmul(maps, p, dt, X, ldx, Y, ldy, C, ldc, accumulate ? 1 : 0,
+                                         static_cast<hipStream_t>(hip_stream));
+        e != hipSuccess) {
+        note_device_error("masked GEMM launch", e);
         return MMM_ERR_DEVICE;
+    }
     return MMM_OK;
 }
 
@@ -285,6 +303,8 @@ mmm_status mmm_set_option(const char *name, int64_t value)
     }
     return MMM_ERR_INVALID_ARG;
 }
+
+const char *mmm_last_device_error(void) { return g_detail; }
 
 int32_t mmm_matmul_variant_count(void) { return mmm_variant_count(); }
 

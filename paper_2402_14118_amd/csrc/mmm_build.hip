@@ -228,6 +228,7 @@ hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStrea
     if (n_a + n_b <= 0 || n_a + n_b > 0x7fffffffLL) return hipErrorInvalidValue;
     p.n_a = (uint32_t)n_a;
     const dim3 grid((uint32_t)(n_a + n_b)), block(BUILD_THREADS);
+    (void)hipGetLastError();   // drop any stale error another library left on this thread
     if (a.dtype == MMM_BF16)
         hipLaunchKernelGGL(mmm_build_kernel<uint16_t>, grid, block, 0, s, p);
     else
@@ -237,6 +238,7 @@ hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStrea
 
 hipError_t mmm_launch_stats(const mmm_maps *m, hipStream_t s)
 {
+    (void)hipGetLastError();
     hipLaunchKernelGGL(mmm_stats_clear_kernel, dim3(1), dim3(64), 0, s, m->stats);
     hipLaunchKernelGGL(mmm_stats_kernel, dim3((uint32_t)m->WA), dim3(256), 0, s, m->a_bits, m->b_bits, m->M,
                        m->K, m->WA, m->WB, (int64_t)m->bw, m->stats);

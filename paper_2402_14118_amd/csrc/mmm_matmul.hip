@@ -329,6 +329,7 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtyp
     if (pl.split_k > 1 && (size_t)pl.split_k * (size_t)m->M * (size_t)m->N * sizeof(float) > m->partial_bytes)
         return hipErrorInvalidValue;
     matmul_kernel_fn fn = dtype == MMM_BF16 ? v.bf16 : v.f32;
+    (void)hipGetLastError();   // drop any stale error another library left on this thread
     hipLaunchKernelGGL(fn, dim3((uint32_t)pl.workgroups), dim3((uint32_t)v.info.threads), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
