@@ -103,6 +103,7 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
     const int64_t nb_left = p.NB - w * 64;
     const uint64_t valid = nb_left >= 64 ? ~0ull : ((1ull << nb_left) - 1ull);
     uint32_t piece_bits = 0;
+#pragma unroll 1
     for (int r = 0; r < B_ROWS_PER_WAVE; ++r) {
         const int64_t k = kbase + r;
         uint64_t word = 0;
@@ -112,18 +113,22 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
             if (p.keep_blocks != nullptr) kept &= p.keep_blocks[k * p.WB + w];
             if (kept != 0) {
                 const T *row = Y + k * p.ldy + w * 64 * BW;
-                uint32_t u[BW];
-#pragma unroll
-                for (int j = 0; j < BW; ++j) {
-                    const int blk = j * BPL + lane / BW;   // block (inside this word) of this lane's element
-                    u[j] = 0;
-                    if ((kept >> blk) & 1ull) u[j] = f32_bits<T>(row[j * 64 + lane]);
-                }
+                constexpr int BATCH = 8;   // loads in flight per lane
                 uint64_t mine = 0;
+#pragma unroll 1
+                for (int j0 = 0; j0 < BW; j0 += BATCH) {
+                    uint32_t u[BATCH];
 #pragma unroll
-                for (int j = 0; j < BW; ++j) {
-                    const uint64_t m = ballot64((u[j] & 0x7fffffffu) != 0);
-                    if (lane / BPL == j) mine = m;   // lane L collects the load that holds block L
+                    for (int j = 0; j < BATCH; ++j) {
+                        const int blk = (j0 + j) * BPL + lane / BW;   // block (inside this word) of this lane's element
+                        u[j] = 0;
+                        if ((kept >> blk) & 1ull) u[j] = f32_bits<T>(row[(j0 + j) * 64 + lane]);
+                    }
+#pragma unroll
+                    for (int j = 0; j < BATCH; ++j) {
+                        const uint64_t m = ballot64((u[j] & 0x7fffffffu) != 0);
+                        if (lane / BPL == j0 + j) mine = m;   // lane L collects the load that holds block L
+                    }
                 }
                 const uint64_t bwmask = BW == 32 ? 0xffffffffull : ((1ull << BW) - 1ull);
                 word = ballot64(((mine >> ((lane % BPL) * BW)) & bwmask) != 0);

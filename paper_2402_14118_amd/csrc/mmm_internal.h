@@ -12,6 +12,8 @@ constexpr int MMM_COLANY_ROWS = 32;
 // Rows of B (values of k) one workgroup of the B-side map builder covers; the
 // transposed map is written in pieces of this many bits.
 constexpr int MMM_BT_PIECE = 16;
+// Dynamic LDS the masked GEMM may use for map words (static use stays below 44 KiB).
+constexpr int MMM_MAX_DYN_LDS = 20 * 1024;
 
 struct mmm_maps {
     int64_t M, K, N;
@@ -61,7 +63,7 @@ struct mmm_plan {
 
 struct mmm_variant_info {
     const char *name;
-    int32_t TM, TN, KC, threads;
+    int32_t TM, TN, KC, threads, groups;
 };
 
 hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStream_t s);

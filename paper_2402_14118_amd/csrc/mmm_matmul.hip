@@ -14,10 +14,16 @@
 // tile is zero (column-any words).  The iteration over the list is uniform
 // across the wave: no lane-divergent branch exists in the inner loop.
 //
-// Data movement: the A slab of a K-chunk (TM rows x KC columns, masked) is
-// staged once per workgroup in LDS and shared by all of its waves; occupied B
-// blocks go straight from global memory into the MFMA operand register and are
-// reused for all TM/16 row sub-tiles of the wave.
+// Data movement.  K is walked in chunks of KC.  The masked A slab of a chunk
+// (TM rows x KC columns) is staged once per workgroup in LDS and shared by all
+// of its waves; occupied B blocks go straight from global memory into the MFMA
+// operand register and are reused for all TM/16 row sub-tiles of the wave.  The
+// loop is software-pipelined by one chunk: while chunk c is multiplied, the A
+// slab of chunk c+1 is already in flight into registers, the lists of chunk c+1
+// are built, and its first B operands are in flight too; inside a list the B
+// operands of the next batch are requested before the current batch is
+// multiplied.  The map words a workgroup needs are copied to LDS in windows of
+// many chunks, so building a list never waits on global memory.
 #include "mmm_internal.h"
 
 namespace {
@@ -39,6 +45,7 @@ struct MatmulParams {
     int64_t M, K, N, NB, WA, WB, MT;
     int32_t bw;
     int32_t tiles_m, tiles_n, split_k, chunks_total, chunks_per_split;
+    int32_t window_chunks;   // chunks whose map words are held in LDS at a time
     int32_t accumulate;
     int32_t fast_x;   // X rows are 16-byte (f32) / 8-byte (bf16) aligned: vector loads allowed
 };
@@ -79,6 +86,8 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v)
     return ((uint64_t)hi << 32) | lo;
 }
 
+extern __shared__ uint64_t mmm_dyn_words[];   // [NG + 1][nwords]: transposed-B words per group, then column-any words
+
 // TM  rows of C per workgroup (shared by all its waves), multiple of 32
 // GW  16-column groups per wave, NW waves per workgroup: TN = 16*GW*NW columns
 // KC  columns of A staged per step, multiple of 64
@@ -88,13 +97,16 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     constexpr int RT = TM / 16;      // 16-row MFMA sub-tiles per wave
     constexpr int KCP = KC + 4;      // padded LDS row; columns KC..KC+3 stay zero (list sentinel)
     constexpr int NG = NW * GW;
-    constexpr int QB = 4;            // list quads fetched per batch
+    constexpr int QB = 4;            // list quads per batch
     constexpr int LPAD = 4 * QB;
     constexpr int C4 = KC / 4;
     constexpr int NT = NW * 64;
+    constexpr int APT = TM * C4 / NT;   // float4 items of the A slab per thread
+    constexpr int WPC = KC / 64;        // map words per chunk
+    static_assert(TM * C4 % NT == 0, "A slab must divide evenly over the threads");
 
     __shared__ __align__(16) float As[TM * KCP];
-    __shared__ uint16_t lists[NG][KC + LPAD];
+    __shared__ uint16_t lists[2][NG][KC + LPAD];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -108,6 +120,7 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     const int64_t row0 = (int64_t)tile_m * TM;
     const int chunk_begin = split * p.chunks_per_split;
     const int chunk_end = min(chunk_begin + p.chunks_per_split, p.chunks_total);
+    const int nwords = p.window_chunks * WPC;
 
     const T *X = static_cast<const T *>(p.X);
     const T *Y = static_cast<const T *>(p.Y);
@@ -118,109 +131,197 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
 #pragma unroll
         for (int r = 0; r < RT; ++r) acc[g][r] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // zero pad columns once
     for (int r = tid; r < TM; r += NT) *reinterpret_cast<floatx4 *>(&As[r * KCP + KC]) = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    for (int chunk = chunk_begin; chunk < chunk_end; ++chunk) {
-        const int64_t k0 = (int64_t)chunk * KC;
-        __syncthreads();   // all waves are done reading the previous chunk
-
-        // ---- stage the masked A slab: As[r][kk] = a_bits[row0+r, k0+kk] ? X[row0+r, k0+kk] : 0
-        for (int idx = tid; idx < TM * C4; idx += NT) {
-            const int r = idx / C4, c4 = idx % C4;
-            const int64_t row = row0 + r, k = k0 + 4 * c4;
-            floatx4 v = {0.f, 0.f, 0.f, 0.f};
-            if (row < p.M && k < p.K) {
-                const uint32_t nib = (p.a_bytes[row * p.WA * 8 + (k >> 3)] >> (k & 4)) & 0xFu;
-                if (nib) {   // pad bits are zero, so a set bit implies k+e < K
-                    const T *src = X + row * p.ldx + k;
-                    if (p.fast_x && k + 3 < p.K) {
-                        v = load4<T>(src);
-                    } else {
-                        if (nib & 1u) v.x = to_f32<T>(src[0]);
-                        if (nib & 2u) v.y = to_f32<T>(src[1]);
-                        if (nib & 4u) v.z = to_f32<T>(src[2]);
-                        if (nib & 8u) v.w = to_f32<T>(src[3]);
+    // map words of the chunks [wbegin, wbegin + window_chunks) -> LDS
+    auto load_words = [&](int wbegin) {
+        for (int idx = tid; idx < (NG + 1) * nwords; idx += NT) {
+            const int gi = idx / nwords, wi = idx % nwords;
+            const int64_t widx = (int64_t)wbegin * WPC + wi;
+            uint64_t m = 0;
+            if (widx < p.WA) {
+                if (gi < NG) {
+                    const int64_t G = (int64_t)tile_n * NG + gi;   // global 16-column group
+                    if (G * 16 < p.N) {
+                        if (p.bw == 16) {
+                            m = p.bt_bits[G * p.WA + widx];
+                        } else if (p.bw == 32) {
+                            m = p.bt_bits[(G >> 1) * p.WA + widx];
+                        } else {
+                            m = p.bt_bits[(2 * G) * p.WA + widx];
+                            if (2 * G + 1 < p.NB) m |= p.bt_bits[(2 * G + 1) * p.WA + widx];
+                        }
                     }
-                    if (!(nib & 1u)) v.x = 0.f;
-                    if (!(nib & 2u)) v.y = 0.f;
-                    if (!(nib & 4u)) v.z = 0.f;
-                    if (!(nib & 8u)) v.w = 0.f;
-                }
-            }
-            *reinterpret_cast<floatx4 *>(&As[r * KCP + 4 * c4]) = v;
-        }
-
-        // ---- per 16-column group: compact list of the k of this chunk that are live
-        int cnt[GW];
-#pragma unroll
-        for (int g = 0; g < GW; ++g) {
-            const int64_t G = (int64_t)tile_n * NG + wave * GW + g;   // global group index
-            const int64_t col0 = G * 16;
-            int base = 0;
-#pragma unroll
-            for (int wd = 0; wd < KC / 64; ++wd) {
-                const int64_t widx = k0 / 64 + wd;
-                uint64_t m = 0;
-                if (widx < p.WA && col0 < p.N) {
-                    if (p.bw == 16) {
-                        m = p.bt_bits[G * p.WA + widx];
-                    } else if (p.bw == 32) {
-                        m = p.bt_bits[(G >> 1) * p.WA + widx];
-                    } else {
-                        m = p.bt_bits[(2 * G) * p.WA + widx];
-                        if (2 * G + 1 < p.NB) m |= p.bt_bits[(2 * G + 1) * p.WA + widx];
-                    }
-                    uint64_t any = 0;
+                } else {
 #pragma unroll
                     for (int t = 0; t < TM / MMM_COLANY_ROWS; ++t) {
                         const int64_t tt = row0 / MMM_COLANY_ROWS + t;
-                        if (tt < p.MT) any |= p.a_colany[tt * p.WA + widx];
+                        if (tt < p.MT) m |= p.a_colany[tt * p.WA + widx];
                     }
-                    m = uniform64(m & any);
                 }
-                const uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                if ((m >> lane) & 1ull) lists[wave * GW + g][base + pos] = (uint16_t)(wd * 64 + lane);
-                base += __popcll(m);
             }
-            if (lane < LPAD) lists[wave * GW + g][base + lane] = (uint16_t)KC;
-            cnt[g] = base;
+            mmm_dyn_words[idx] = m;
         }
-        __syncthreads();
+    };
 
-        // ---- walk the lists: 4 k per MFMA, B operand straight from global memory
+    int wbegin = chunk_begin;   // first chunk of the current window
+    floatx4 areg[APT];
+    uint32_t anib[APT];
+    float bcur[GW][QB], bnext[GW][QB];
+    int cnt_cur[GW], cnt_next[GW];
+
+    // request the A slab of chunk ci (relative) into registers
+    auto issue_a = [&](int ci) {
+        const int64_t k0 = (int64_t)(wbegin + ci) * KC;
+#pragma unroll
+        for (int i = 0; i < APT; ++i) {
+            const int idx = tid + i * NT;
+            const int r = idx / C4, c4 = idx % C4;
+            const int64_t row = row0 + r, k = k0 + 4 * c4;
+            floatx4 v = {0.f, 0.f, 0.f, 0.f};
+            uint32_t nib = 0;
+            if (row < p.M && k < p.K) {
+                nib = (p.a_bytes[row * p.WA * 8 + (k >> 3)] >> (k & 4)) & 0xFu;
+                const T *src = X + row * p.ldx + k;
+                if (p.fast_x && k + 3 < p.K) {
+                    v = load4<T>(src);
+                } else {   // pad bits of the map are zero, so a set bit implies k+e < K
+                    if (nib & 1u) v.x = to_f32<T>(src[0]);
+                    if (nib & 2u) v.y = to_f32<T>(src[1]);
+                    if (nib & 4u) v.z = to_f32<T>(src[2]);
+                    if (nib & 8u) v.w = to_f32<T>(src[3]);
+                }
+            }
+            areg[i] = v;
+            anib[i] = nib;
+        }
+    };
+    // As[r][kk] = a_bits[row0+r, k0+kk] ? X[row0+r, k0+kk] : 0
+    auto store_a = [&]() {
+#pragma unroll
+        for (int i = 0; i < APT; ++i) {
+            const int idx = tid + i * NT;
+            const int r = idx / C4, c4 = idx % C4;
+            floatx4 v = areg[i];
+            const uint32_t nib = anib[i];
+            if (!(nib & 1u)) v.x = 0.f;
+            if (!(nib & 2u)) v.y = 0.f;
+            if (!(nib & 4u)) v.z = 0.f;
+            if (!(nib & 8u)) v.w = 0.f;
+            *reinterpret_cast<floatx4 *>(&As[r * KCP + 4 * c4]) = v;
+        }
+    };
+    // per 16-column group: compacted list of the live k of chunk ci (chunk-relative, ascending)
+    auto build_lists = [&](int ci, int buf, int (&cnt)[GW]) {
 #pragma unroll
         for (int g = 0; g < GW; ++g) {
-            const int n = cnt[g];
-            const int64_t col = ((int64_t)tile_n * NG + wave * GW + g) * 16 + c;
-            const bool col_ok = col < p.N;
-            const uint16_t *lst = lists[wave * GW + g];
-            const T *Ycol = Y + k0 * p.ldy + col;
-            for (int q = 0; q < n; q += LPAD) {
-                int kk[QB];
+            const int gi = wave * GW + g;
+            int base = 0;
+#pragma unroll
+            for (int wd = 0; wd < WPC; ++wd) {
+                const int wi = ci * WPC + wd;
+                const uint64_t m = uniform64(mmm_dyn_words[gi * nwords + wi] & mmm_dyn_words[NG * nwords + wi]);
+                const uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                if ((m >> lane) & 1ull) lists[buf][gi][base + pos] = (uint16_t)(wd * 64 + lane);
+                base += __popcll(m);
+            }
+            if (lane < LPAD) lists[buf][gi][base + lane] = (uint16_t)KC;
+            cnt[g] = base;
+        }
+    };
+    // one B operand: row k0+kk of Y at this lane's column, or 0 for a list sentinel
+    auto load_b = [&](int64_t k0, int kk, int64_t col, bool col_ok) -> float {
+        bool ok = col_ok && kk < KC;
+        if (p.bw == 8 && ok) {   // a group spans two blocks: take only this lane's own block
+            const int64_t blk = col >> 3;
+            ok = (p.b_bits[(k0 + kk) * p.WB + (blk >> 6)] >> (blk & 63)) & 1ull;
+        }
+        return ok ? to_f32<T>(Y[(k0 + kk) * p.ldy + col]) : 0.f;
+    };
+    auto issue_b_first = [&](int ci, int buf, float (&b)[GW][QB]) {
+        const int64_t k0 = (int64_t)(wbegin + ci) * KC;
+#pragma unroll
+        for (int g = 0; g < GW; ++g) {
+            const int gi = wave * GW + g;
+            const int64_t col = ((int64_t)tile_n * NG + gi) * 16 + c;
+#pragma unroll
+            for (int u = 0; u < QB; ++u) b[g][u] = load_b(k0, lists[buf][gi][4 * u + s], col, col < p.N);
+        }
+    };
+
+    // K range of this workgroup, in windows whose map words fit in LDS; inside a window the
+    // chunk loop is pipelined by one chunk
+    for (wbegin = chunk_begin; wbegin < chunk_end; wbegin += p.window_chunks) {
+        const int nchunks = min(p.window_chunks, chunk_end - wbegin);
+        __syncthreads();   // previous window fully consumed (A slab and map words)
+        load_words(wbegin);
+        __syncthreads();
+        build_lists(0, 0, cnt_cur);
+        issue_a(0);
+        issue_b_first(0, 0, bcur);
+        store_a();
+        __syncthreads();
+
+
+        for (int ci = 0; ci < nchunks; ++ci) {
+            const int buf = ci & 1;
+            const bool has_next = ci + 1 < nchunks;
+            const int64_t k0 = (int64_t)(wbegin + ci) * KC;
+            if (has_next) {
+                build_lists(ci + 1, buf ^ 1, cnt_next);
+                issue_a(ci + 1);
+                issue_b_first(ci + 1, buf ^ 1, bnext);
+            }
+
+            // ---- multiply chunk ci: 4 listed k per MFMA
+    #pragma unroll
+            for (int g = 0; g < GW; ++g) {
+                const int n = cnt_cur[g];
+                const int gi = wave * GW + g;
+                const int64_t col = ((int64_t)tile_n * NG + gi) * 16 + c;
+                const bool col_ok = col < p.N;
+                const uint16_t *lst = lists[buf][gi];
                 float b[QB];
-#pragma unroll
-                for (int u = 0; u < QB; ++u) kk[u] = lst[q + 4 * u + s];
-#pragma unroll
-                for (int u = 0; u < QB; ++u) {
-                    bool ok = col_ok && kk[u] < KC;
-                    if (p.bw == 8 && ok) {   // a group spans two blocks: take only this lane's own block
-                        const int64_t blk = col >> 3;
-                        ok = (p.b_bits[(k0 + kk[u]) * p.WB + (blk >> 6)] >> (blk & 63)) & 1ull;
+    #pragma unroll
+                for (int u = 0; u < QB; ++u) b[u] = bcur[g][u];
+                for (int q = 0; q < n; q += LPAD) {
+                    float bn[QB];
+                    if (q + LPAD < n) {   // request the next batch of B operands before multiplying this one
+    #pragma unroll
+                        for (int u = 0; u < QB; ++u) bn[u] = load_b(k0, lst[q + LPAD + 4 * u + s], col, col_ok);
+                    } else {
+    #pragma unroll
+                        for (int u = 0; u < QB; ++u) bn[u] = 0.f;
                     }
-                    b[u] = ok ? to_f32<T>(Ycol[(int64_t)kk[u] * p.ldy]) : 0.f;
-                }
-#pragma unroll
-                for (int u = 0; u < QB; ++u) {
-                    if (q + 4 * u < n) {
-#pragma unroll
-                        for (int r = 0; r < RT; ++r) {
-                            const float a = As[(r * 16 + c) * KCP + kk[u]];
-                            acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[u], acc[g][r], 0, 0, 0);
+                    int kk[QB];
+    #pragma unroll
+                    for (int u = 0; u < QB; ++u) kk[u] = lst[q + 4 * u + s];
+    #pragma unroll
+                    for (int u = 0; u < QB; ++u) {
+                        if (q + 4 * u < n) {
+    #pragma unroll
+                            for (int r = 0; r < RT; ++r) {
+                                const float a = As[(r * 16 + c) * KCP + kk[u]];
+                                acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[u], acc[g][r], 0, 0, 0);
+                            }
                         }
                     }
+    #pragma unroll
+                    for (int u = 0; u < QB; ++u) b[u] = bn[u];
                 }
             }
+
+            __syncthreads();   // every wave is done reading the A slab of chunk ci
+            if (has_next) {
+                store_a();
+    #pragma unroll
+                for (int g = 0; g < GW; ++g) {
+                    cnt_cur[g] = cnt_next[g];
+    #pragma unroll
+                    for (int u = 0; u < QB; ++u) bcur[g][u] = bnext[g][u];
+                }
+            }
+            __syncthreads();   // the A slab of chunk ci+1 is complete
         }
     }
 
@@ -272,7 +373,7 @@ struct VariantEntry {
 
 #define MMM_VARIANT(TM, GW, NW, KC)                                                                        \
     {                                                                                                      \
-        {"TM" #TM "_TN" #GW "x" #NW "x16_KC" #KC, TM, 16 * GW * NW, KC, NW * 64},                          \
+        {"TM" #TM "_TN" #GW "x" #NW "x16_KC" #KC, TM, 16 * GW * NW, KC, NW * 64, NW * GW},                 \
             mmm_matmul_kernel<TM, GW, NW, KC, float>, mmm_matmul_kernel<TM, GW, NW, KC, uint16_t>          \
     }
 
@@ -281,9 +382,10 @@ const VariantEntry g_variants[] = {
     MMM_VARIANT(64, 2, 4, 128),    // 1: 64 x 128
     MMM_VARIANT(32, 4, 4, 128),    // 2: 32 x 256
     MMM_VARIANT(32, 2, 4, 256),    // 3: 32 x 128, long chunk
-    MMM_VARIANT(128, 4, 4, 64),    // 4: 128 x 256
-    MMM_VARIANT(64, 4, 4, 64),     // 5: 64 x 256, short chunk
-    MMM_VARIANT(32, 1, 4, 256),    // 6: 32 x 64
+    MMM_VARIANT(128, 2, 4, 64),    // 4: 128 x 128, short chunk
+    MMM_VARIANT(64, 2, 4, 64),     // 5: 64 x 128, short chunk
+    MMM_VARIANT(64, 1, 8, 128),    // 6: 64 x 128, eight waves
+    MMM_VARIANT(32, 1, 4, 256),    // 7: 32 x 64
 };
 constexpr int32_t kVariants = (int32_t)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -328,9 +430,15 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtyp
     if (pl.workgroups <= 0 || pl.workgroups > 0x7fffffffLL) return hipErrorInvalidValue;
     if (pl.split_k > 1 && (size_t)pl.split_k * (size_t)m->M * (size_t)m->N * sizeof(float) > m->partial_bytes)
         return hipErrorInvalidValue;
+    const int64_t wpc = v.info.KC / 64;
+    int64_t window = MMM_MAX_DYN_LDS / (int64_t)((v.info.groups + 1) * wpc * sizeof(uint64_t));
+    if (window > pl.chunks_per_split) window = pl.chunks_per_split;
+    if (window < 1) return hipErrorInvalidValue;
+    p.window_chunks = (int32_t)window;
+    const size_t dyn = (size_t)(v.info.groups + 1) * (size_t)window * (size_t)wpc * sizeof(uint64_t);
     matmul_kernel_fn fn = dtype == MMM_BF16 ? v.bf16 : v.f32;
     (void)hipGetLastError();   // drop any stale error another library left on this thread
-    hipLaunchKernelGGL(fn, dim3((uint32_t)pl.workgroups), dim3((uint32_t)v.info.threads), 0, s, p);
+    hipLaunchKernelGGL(fn, dim3((uint32_t)pl.workgroups), dim3((uint32_t)v.info.threads), dyn, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (pl.split_k > 1) {
