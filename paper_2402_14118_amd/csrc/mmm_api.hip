@@ -11,6 +11,7 @@
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr int64_t kMaxLd = 1LL << 22;   // largest leading dimension of X and Y the masked GEMM addresses
 constexpr size_t kPartialCap = (size_t)64 << 20;   // split-K partial sums: at most 64 MiB
 
 thread_local char g_detail[160] = "";
@@ -26,7 +27,7 @@ std::atomic<int64_t> g_opt_split{0};
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t a_bits, a_colany, b_bits, bt_bits, stats, partials, partial_bytes, total;
+    size_t a_bits, a_colany, a_cnt, a_ent, b_bits, bt_bits, stats, partials, partial_bytes, total;
 };
 
 bool shape_ok(int64_t M, int64_t K, int64_t N, int32_t bw)
@@ -48,6 +49,11 @@ Layout make_layout(int64_t M, int64_t K, int64_t N, int32_t bw)
     off += align_up((size_t)M * WA * 8);
     l.a_colany = off;
     off += align_up((size_t)MT * WA * 8);
+    const size_t blocks = (size_t)((M + MMM_AB_ROWS - 1) / MMM_AB_ROWS) * (size_t)((K + MMM_AB_COLS - 1) / MMM_AB_COLS);
+    l.a_cnt = off;
+    off += align_up(blocks * 4);
+    l.a_ent = off;
+    off += align_up(blocks * MMM_AB_CAP * 8);
     l.b_bits = off;
     off += align_up((size_t)K * WB * 8);
     l.bt_bits = off;
@@ -72,13 +78,16 @@ mmm_plan make_plan(const mmm_maps *m, int32_t dt)
     (void)dt;
     mmm_plan p{};
     int64_t v = g_opt_variant.load();
+    if (v >= 0 && v < mmm_variant_count() && mmm_variant((int32_t)v).rows < MMM_AB_ROWS && m->M > mmm_variant((int32_t)v).rows)
+        v = -1;   // that kernel computes too few rows for this matrix
     if (v < 0 || v >= mmm_variant_count()) {
-        // automatic: row tile from M, column tile from how many workgroups result
+        // automatic: 32-row kernels for short matrices; otherwise the column tile that still
+        // gives every CU several workgroups
         if (m->M <= 32) {
-            v = 2;
+            v = 5;
         } else {
-            const int64_t t64x256 = ((m->M + 63) / 64) * ((m->N + 255) / 256);
-            v = t64x256 >= 1024 ? 0 : 1;
+            const int64_t t128 = ((m->M + 63) / 64) * ((m->N + 127) / 128);
+            v = t128 >= 4096 ? 1 : 0;
         }
     }
     const mmm_variant_info &vi = mmm_variant((int32_t)v);
@@ -151,6 +160,10 @@ mmm_status mmm_maps_init(void *dev_workspace, size_t workspace_bytes, int64_t M,
     char *base = static_cast<char *>(dev_workspace);
     m->a_bits = reinterpret_cast<uint64_t *>(base + l.a_bits);
     m->a_colany = reinterpret_cast<uint64_t *>(base + l.a_colany);
+    m->MBA = (M + MMM_AB_ROWS - 1) / MMM_AB_ROWS;
+    m->KBA = (K + MMM_AB_COLS - 1) / MMM_AB_COLS;
+    m->a_cnt = reinterpret_cast<uint32_t *>(base + l.a_cnt);
+    m->a_ent = reinterpret_cast<uint64_t *>(base + l.a_ent);
     m->b_bits = reinterpret_cast<uint64_t *>(base + l.b_bits);
     m->bt_bits = reinterpret_cast<uint64_t *>(base + l.bt_bits);
     m->stats = reinterpret_cast<uint64_t *>(base + l.stats);
@@ -272,6 +285,7 @@ mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t
     if (maps == nullptr || X == nullptr || Y == nullptr || C == nullptr) return MMM_ERR_INVALID_ARG;
     if (!dtype_ok(dt)) return MMM_ERR_DTYPE;
     if (ldx < maps->K || ldy < maps->N || ldc < maps->N) return MMM_ERR_SHAPE;
+    if (ldx > kMaxLd || ldy > kMaxLd) return MMM_ERR_SHAPE;   // tile-relative offsets are 32-bit
     const size_t esz = elem_size(dt);
     if (reinterpret_cast<uintptr_t>(X) % esz != 0 || reinterpret_cast<uintptr_t>(Y) % esz != 0 ||
         reinterpret_cast<uintptr_t>(C) % sizeof(float) != 0)

@@ -1,8 +1,15 @@
 // Map builder: evaluates the masks M and N on the device and writes the
 // sparsity maps (paper, section 3 "Preprocessing": a single sequential, aligned
-// pass; one bit per vector of B, 1 = some non-zero value; the non-zero positions
-// of A per row).  Everything here is integer work on float bit patterns, bound
-// by HBM bandwidth.
+// pass per matrix).  Everything here is integer work on float bit patterns,
+// bound by HBM bandwidth.
+//
+// A side (section 3 "Optimizations", Fig. "Blocked sparse row preprocessing"):
+// per block of 64 rows x 128 columns the count of non-zero elements and their
+// positions inside the block, here together with the values, in row-major order;
+// plus the plain non-zero bitmap and its column-any summary.
+// B side (section 3 "Block-Random Sparsity in B", Fig. "Preprocessing
+// patterns"): one bit per block, 1 = some non-zero value; plus the same map
+// transposed to one bit-row per block column.
 //
 // One launch covers both matrices: the first n_a workgroups scan X, the rest
 // scan Y.  Every output word has exactly one producer, so there are no atomics
@@ -12,7 +19,8 @@
 namespace {
 
 constexpr int BUILD_THREADS = 256;
-constexpr int A_ROWS_PER_WAVE = MMM_COLANY_ROWS / 4;   // 8
+constexpr int A_ROWS_PER_WAVE = MMM_AB_ROWS / 4;       // 16
+constexpr int A_WORDS = MMM_AB_COLS / 64;              // 2
 constexpr int B_ROWS_PER_WAVE = MMM_BT_PIECE / 4;      // 4
 
 struct BuildParams {
@@ -21,13 +29,15 @@ struct BuildParams {
     const uint64_t *keep_a;
     uint64_t *a_bits;
     uint64_t *a_colany;
+    uint32_t *a_cnt;
+    uint2 *a_ent;
     const void *Y;
     int64_t ldy;
     const uint64_t *keep_rows;
     const uint64_t *keep_blocks;
     uint64_t *b_bits;
     uint16_t *bt16;
-    int64_t M, K, N, NB, WA, WB;
+    int64_t M, K, N, NB, WA, WB, MT, KBA;
     uint32_t thr_bits;
     int32_t pred;
     uint32_t n_a;   // workgroups that scan X
@@ -62,34 +72,94 @@ __device__ __forceinline__ bool keep_element(uint32_t u, int32_t pred, uint32_t 
 
 __device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
 
-// ---- A side: one workgroup = 32 rows x 64 columns --------------------------------------------
-template <typename T>
-__device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lane, int wave, uint64_t *red)
+__device__ __forceinline__ uint32_t mbcnt64(uint64_t m)
 {
-    const int64_t t = b / p.WA, w = b % p.WA;
-    const int64_t k = w * 64 + lane;
-    const int64_t rbase = t * MMM_COLANY_ROWS + wave * A_ROWS_PER_WAVE;
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+// ---- A side: one workgroup = one block of 64 rows x 128 columns ------------------------------
+// Wave w scans rows 16w..16w+15, one 64-column word per load.  Lane 2j+h of the wave ends up
+// holding the bitmap word (row j, half h); entries are appended in (row, column) order.
+template <typename T>
+__device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lane, int wave, uint64_t *red,
+                                       uint32_t *tot)
+{
+    const int64_t bi = b / p.KBA, bj = b % p.KBA;
+    const int64_t k_lo = bj * MMM_AB_COLS;
+    const int64_t rbase = bi * MMM_AB_ROWS + wave * A_ROWS_PER_WAVE;
+    const int64_t w_lo = k_lo / 64;
     const T *X = static_cast<const T *>(p.X);
-    uint32_t u[A_ROWS_PER_WAVE];
+    uint32_t u[A_ROWS_PER_WAVE][A_WORDS];
 #pragma unroll
     for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
-        const int64_t r = rbase + j;
-        u[j] = 0;
-        if (r < p.M && k < p.K) u[j] = f32_bits<T>(X[r * p.ldx + k]);
+#pragma unroll
+        for (int h = 0; h < A_WORDS; ++h) {
+            const int64_t r = rbase + j, k = k_lo + 64 * h + lane;
+            u[j][h] = 0;
+            if (r < p.M && k < p.K) u[j][h] = f32_bits<T>(X[r * p.ldx + k]);
+        }
     }
-    uint64_t colany = 0, mine = 0;
+    uint64_t colany[A_WORDS] = {0, 0}, mine = 0;
 #pragma unroll
     for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
-        const int64_t r = rbase + j;
-        uint64_t m = ballot64(keep_element(u[j], p.pred, p.thr_bits));   // lanes past K or M hold +0
-        if (p.keep_a != nullptr && r < p.M) m &= p.keep_a[r * p.WA + w];
-        colany |= m;
-        if (lane == j) mine = m;
+#pragma unroll
+        for (int h = 0; h < A_WORDS; ++h) {
+            const int64_t r = rbase + j;
+            uint64_t m = ballot64(keep_element(u[j][h], p.pred, p.thr_bits));   // lanes past K or M hold +0
+            if (p.keep_a != nullptr && m != 0) m &= p.keep_a[r * p.WA + w_lo + h];   // m != 0: r < M and the word exists
+            colany[h] |= m;
+            if (lane == 2 * j + h) mine = m;
+        }
     }
-    if (lane < A_ROWS_PER_WAVE && rbase + lane < p.M) p.a_bits[(rbase + lane) * p.WA + w] = mine;
-    if (lane == 0) red[wave] = colany;
+    // bitmap words and per-wave entry offsets
+    const bool have_word = lane < 2 * A_ROWS_PER_WAVE && rbase + (lane >> 1) < p.M && w_lo + (lane & 1) < p.WA;
+    if (have_word) p.a_bits[(rbase + (lane >> 1)) * p.WA + w_lo + (lane & 1)] = mine;
+    const uint32_t my_cnt = (uint32_t)__popcll(mine);   // lanes >= 32 hold 0
+    uint32_t incl = my_cnt;
+#pragma unroll
+    for (int d = 1; d < 32; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    const uint32_t excl = incl - my_cnt;
+    if (lane == 31) tot[wave] = incl;
+    if (lane == 0) {
+        red[wave * A_WORDS + 0] = colany[0];
+        red[wave * A_WORDS + 1] = colany[1];
+    }
     __syncthreads();
-    if (threadIdx.x == 0) p.a_colany[t * p.WA + w] = red[0] | red[1] | red[2] | red[3];
+    uint32_t base = 0;
+    for (int w = 0; w < wave; ++w) base += tot[w];
+    if (threadIdx.x == 0) p.a_cnt[b] = tot[0] + tot[1] + tot[2] + tot[3];
+    if (threadIdx.x < 2 * A_WORDS) {   // column-any words of the two 32-row tiles of this block
+        const int t = threadIdx.x >> 1, h = threadIdx.x & 1;
+        const int64_t tile = bi * (MMM_AB_ROWS / MMM_COLANY_ROWS) + t;
+        if (tile < p.MT && w_lo + h < p.WA)
+            p.a_colany[tile * p.WA + w_lo + h] = red[(2 * t) * A_WORDS + h] | red[(2 * t + 1) * A_WORDS + h];
+    }
+    // compacted entries {byte offset inside the multiplier's LDS slab, value}, in (row, column) order
+    uint2 *ent = p.a_ent + (size_t)b * MMM_AB_CAP;
+#pragma unroll
+    for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
+#pragma unroll
+        for (int h = 0; h < A_WORDS; ++h) {
+            const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)mine, 2 * j + h);
+            const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(mine >> 32), 2 * j + h);
+            const uint64_t m = ((uint64_t)hi << 32) | lo;
+            if (m == 0) continue;
+            const uint32_t off = base + __builtin_amdgcn_readlane(excl, 2 * j + h);
+            if ((m >> lane) & 1ull) {
+                const uint32_t slab = (uint32_t)((wave * A_ROWS_PER_WAVE + j) * MMM_SLAB_LD + 64 * h + lane) * 4u;
+                ent[off + mbcnt64(m)] = make_uint2(slab, u[j][h]);
+            }
+        }
+    }
+    // pad the list to a whole number of wavefronts with entries that write 0 to a spare slab cell
+    if (wave == 3) {
+        const uint32_t total = base + tot[3];
+        const uint32_t e = total + lane;
+        if (e < ((total + 63u) & ~63u)) ent[e] = make_uint2((uint32_t)MMM_AB_COLS * 4u, 0u);
+    }
 }
 
 // ---- B side: one workgroup = 16 rows (values of k) x 64 blocks -------------------------------
@@ -149,13 +219,14 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
 template <typename T>
 __global__ __launch_bounds__(BUILD_THREADS) void mmm_build_kernel(const BuildParams p)
 {
-    __shared__ uint64_t red[4];
+    __shared__ uint64_t red[4 * A_WORDS];
+    __shared__ uint32_t tot[4];
     __shared__ uint32_t pieces[4 * 64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t b = blockIdx.x;
     if (b < p.n_a) {
-        scan_a<T>(p, b, lane, wave, red);
+        scan_a<T>(p, b, lane, wave, red, tot);
     } else {
         const int64_t bw = p.N / p.NB;
         if (bw == 8)
@@ -212,6 +283,8 @@ hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStrea
     p.keep_a = a.keep_a;
     p.a_bits = m->a_bits;
     p.a_colany = m->a_colany;
+    p.a_cnt = m->a_cnt;
+    p.a_ent = reinterpret_cast<uint2 *>(m->a_ent);
     p.Y = a.Y;
     p.ldy = a.ldy;
     p.keep_rows = a.keep_rows;
@@ -224,11 +297,13 @@ hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStrea
     p.NB = m->NB;
     p.WA = m->WA;
     p.WB = m->WB;
+    p.MT = m->MT;
+    p.KBA = m->KBA;
     p.pred = a.pred;
     union { float f; uint32_t u; } cv;
     cv.f = a.threshold;
     p.thr_bits = cv.u;
-    const int64_t n_a = a.X ? m->MT * m->WA : 0;
+    const int64_t n_a = a.X ? m->MBA * m->KBA : 0;
     const int64_t n_b = a.Y ? (m->WA * (64 / MMM_BT_PIECE)) * m->WB : 0;
     if (n_a + n_b <= 0 || n_a + n_b > 0x7fffffffLL) return hipErrorInvalidValue;
     p.n_a = (uint32_t)n_a;

@@ -12,6 +12,12 @@ constexpr int MMM_COLANY_ROWS = 32;
 // Rows of B (values of k) one workgroup of the B-side map builder covers; the
 // transposed map is written in pieces of this many bits.
 constexpr int MMM_BT_PIECE = 16;
+// Geometry of the blocks of A whose non-zero elements are listed (count, offsets, values).
+constexpr int MMM_AB_ROWS = 64;
+constexpr int MMM_AB_COLS = 128;
+constexpr int MMM_AB_CAP = MMM_AB_ROWS * MMM_AB_COLS;   // list capacity per block: the worst case
+// Row pitch (floats) of the LDS slab a block is scattered into; cell (0, MMM_AB_COLS) is spare.
+constexpr int MMM_SLAB_LD = MMM_AB_COLS + 4;
 // Dynamic LDS the masked GEMM may use for map words (static use stays below 44 KiB).
 constexpr int MMM_MAX_DYN_LDS = 20 * 1024;
 
@@ -22,9 +28,13 @@ struct mmm_maps {
     int64_t WA;        // ceil(K/64): words per row of a_bits, a_colany and bt_bits
     int64_t WB;        // ceil(NB/64): words per row of b_bits
     int64_t MT;        // ceil(M/32): rows of a_colany
+    int64_t MBA, KBA;  // blocks of A: ceil(M/64) x ceil(K/128)
     // device pointers into the caller's workspace
     uint64_t *a_bits;
     uint64_t *a_colany;
+    uint32_t *a_cnt;   // [MBA][KBA] non-zeros per block
+    uint64_t *a_ent;   // [MBA*KBA][MMM_AB_CAP] entries {byte offset row * MMM_SLAB_LD + column in the slab, value bits},
+                       // padded to a multiple of 64 with {spare cell, 0}
     uint64_t *b_bits;
     uint64_t *bt_bits;
     uint64_t *stats;   // 4 words
@@ -63,7 +73,7 @@ struct mmm_plan {
 
 struct mmm_variant_info {
     const char *name;
-    int32_t TM, TN, KC, threads, groups;
+    int32_t TM, TN, KC, threads, groups, rows;   // rows: rows of C actually computed (64, or 32 for short matrices)
 };
 
 hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStream_t s);

@@ -8,105 +8,86 @@
 // from the transposed B map, so the wave walks a *compacted* list of k: every
 // step takes four listed k, gathers the 4 x 16 slab of occupied B blocks and the
 // matching 16 x 4 slab of A, and issues one 16x16x4 fp32 MFMA per 16 rows.  B's
-// block sparsity is skipped exactly (no unoccupied block is ever loaded or
-// multiplied); A's element sparsity is honoured by zeroing masked elements when
-// the A slab is staged, and by dropping every k whose whole column of the row
-// tile is zero (column-any words).  The iteration over the list is uniform
-// across the wave: no lane-divergent branch exists in the inner loop.
+// block sparsity is skipped exactly: no unoccupied block is ever loaded or
+// multiplied.  The iteration over the list is uniform across the wave: no
+// lane-divergent branch exists in the inner loop.
 //
-// Data movement.  K is walked in chunks of KC.  The masked A slab of a chunk
-// (TM rows x KC columns) is staged once per workgroup in LDS and shared by all
-// of its waves; occupied B blocks go straight from global memory into the MFMA
-// operand register and are reused for all TM/16 row sub-tiles of the wave.  The
-// loop is software-pipelined by one chunk: while chunk c is multiplied, the A
-// slab of chunk c+1 is already in flight into registers, the lists of chunk c+1
-// are built, and its first B operands are in flight too; inside a list the B
-// operands of the next batch are requested before the current batch is
-// multiplied.  The map words a workgroup needs are copied to LDS in windows of
-// many chunks, so building a list never waits on global memory.
+// A's element sparsity is used where it pays on this machine, in data movement:
+// only the non-zero elements of A travel.  The map builder lists, per block of
+// 64 rows x 128 columns, the count of non-zeros with their offsets and values
+// (the blocked sparse row structure of section 3, "Optimizations").  A
+// workgroup owns 64 rows of C; per 128-wide step of k it scatters that block's
+// list into a zeroed LDS slab, which all of its waves then read as the dense
+// 16 x 4 MFMA operand; afterwards it zeroes the same positions again.  Columns
+// of the slab that are zero for all 64 rows are dropped from the k lists
+// (column-any words).
+//
+// Pipeline: while step c is multiplied, the list entries of step c+1 are in
+// flight into registers, the k lists of step c+1 are built, and its first B
+// operands are in flight too; inside a k list the B operands of the next batch
+// are requested before the current batch is multiplied.  The map words and
+// block counts a workgroup needs are copied to LDS in windows of many steps.
 #include "mmm_internal.h"
 
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+constexpr int TM = MMM_AB_ROWS;   // rows of C per workgroup = rows of a block of A
+constexpr int KC = MMM_AB_COLS;   // k per step = columns of a block of A
+constexpr int KCP = KC + 4;       // padded LDS row; columns KC..KC+3 stay zero (k-list sentinel)
+constexpr int WPC = KC / 64;      // map words per step
+constexpr int QB = 4;             // k-list quads per batch
+constexpr int LPAD = 4 * QB;
+constexpr int EPT = 8;            // list entries of A per thread and round
+
 struct MatmulParams {
-    const void *X;
-    int64_t ldx;
     const void *Y;
     int64_t ldy;
     float *C;
     int64_t ldc;
     float *P;   // split-K partial sums, [split][M][N]
-    const uint8_t *a_bytes;
+    const uint32_t *a_cnt;
+    const uint2 *a_ent;
     const uint64_t *a_colany;
     const uint64_t *b_bits;
     const uint64_t *bt_bits;
-    int64_t M, K, N, NB, WA, WB, MT;
+    int64_t M, K, N, NB, WA, WB, MT, KBA;
     int32_t bw;
     int32_t tiles_m, tiles_n, split_k, chunks_total, chunks_per_split;
-    int32_t window_chunks;   // chunks whose map words are held in LDS at a time
+    int32_t window_chunks;   // steps whose map words and counts are held in LDS at a time
     int32_t accumulate;
-    int32_t fast_x;   // X rows are 16-byte (f32) / 8-byte (bf16) aligned: vector loads allowed
 };
 
 template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f32<uint16_t>(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 
-template <typename T> __device__ __forceinline__ floatx4 load4(const T *p);
-template <> __device__ __forceinline__ floatx4 load4<float>(const float *p)
-{
-    return *reinterpret_cast<const floatx4 *>(p);
-}
-template <> __device__ __forceinline__ floatx4 load4<uint16_t>(const uint16_t *p)
-{
-    const uint2 r = *reinterpret_cast<const uint2 *>(p);
-    floatx4 v;
-    v.x = __uint_as_float(r.x << 16);
-    v.y = __uint_as_float(r.x & 0xffff0000u);
-    v.z = __uint_as_float(r.y << 16);
-    v.w = __uint_as_float(r.y & 0xffff0000u);
-    return v;
-}
-
 // Workgroups are dealt round-robin to the 8 XCDs.  Re-number them so that each
 // XCD works on a contiguous range of logical tiles: neighbours in that range
-// share the same rows of X, which then stay in that XCD's L2.
+// share the same block row of A and neighbouring column tiles of B, which then
+// stay in that XCD's L2.
 __device__ __forceinline__ uint32_t xcd_contiguous_id(uint32_t b, uint32_t n)
 {
     const uint32_t x = b & 7u, i = b >> 3, q = n >> 3, rem = n & 7u;
     return x * q + (x < rem ? x : rem) + i;
 }
 
-__device__ __forceinline__ uint64_t uniform64(uint64_t v)
-{
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
+// [NG][nwords] 64-bit words (per group: transposed-B word AND column-any word of A),
+// followed by window_chunks 32-bit block counts
+extern __shared__ uint64_t mmm_dyn_words[];
 
-extern __shared__ uint64_t mmm_dyn_words[];   // [NG + 1][nwords]: transposed-B words per group, then column-any words
-
-// TM  rows of C per workgroup (shared by all its waves), multiple of 32
+// RT  16-row MFMA sub-tiles computed (4: all 64 rows of the block; 2: matrices of at most 32 rows)
 // GW  16-column groups per wave, NW waves per workgroup: TN = 16*GW*NW columns
-// KC  columns of A staged per step, multiple of 64
-template <int TM, int GW, int NW, int KC, typename T>
+template <int RT, int GW, int NW, typename T, bool BW8>
 __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams p)
 {
-    constexpr int RT = TM / 16;      // 16-row MFMA sub-tiles per wave
-    constexpr int KCP = KC + 4;      // padded LDS row; columns KC..KC+3 stay zero (list sentinel)
     constexpr int NG = NW * GW;
-    constexpr int QB = 4;            // list quads per batch
-    constexpr int LPAD = 4 * QB;
-    constexpr int C4 = KC / 4;
     constexpr int NT = NW * 64;
-    constexpr int APT = TM * C4 / NT;   // float4 items of the A slab per thread
-    constexpr int WPC = KC / 64;        // map words per chunk
-    static_assert(TM * C4 % NT == 0, "A slab must divide evenly over the threads");
+    constexpr int ROUND = NT * EPT;   // list entries one round of the workgroup moves
 
     __shared__ __align__(16) float As[TM * KCP];
-    __shared__ uint16_t lists[2][NG][KC + LPAD];
+    __shared__ uint8_t lists[NW][64 * 64 + 4];   // per wave: k lists of its groups for one window
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -121,9 +102,10 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     const int chunk_begin = split * p.chunks_per_split;
     const int chunk_end = min(chunk_begin + p.chunks_per_split, p.chunks_total);
     const int nwords = p.window_chunks * WPC;
+    uint32_t *cnt_lds = reinterpret_cast<uint32_t *>(mmm_dyn_words + NG * nwords);
 
-    const T *X = static_cast<const T *>(p.X);
     const T *Y = static_cast<const T *>(p.Y);
+    const uint32_t ldy32 = (uint32_t)p.ldy;
 
     floatx4 acc[GW][RT];
 #pragma unroll
@@ -131,197 +113,269 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
 #pragma unroll
         for (int r = 0; r < RT; ++r) acc[g][r] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    for (int r = tid; r < TM; r += NT) *reinterpret_cast<floatx4 *>(&As[r * KCP + KC]) = floatx4{0.f, 0.f, 0.f, 0.f};
+    // the slab starts out all zero and every step leaves it all zero again
+    for (int i = tid; i < TM * KCP / 4; i += NT) reinterpret_cast<floatx4 *>(As)[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // map words of the chunks [wbegin, wbegin + window_chunks) -> LDS
-    auto load_words = [&](int wbegin) {
-        for (int idx = tid; idx < (NG + 1) * nwords; idx += NT) {
+    int wbegin = chunk_begin;   // first step of the current window
+
+    // map words and block counts of the steps [wb, wb + window_chunks) -> LDS
+    auto load_words = [&](int wb) {
+        for (int idx = tid; idx < NG * nwords; idx += NT) {
             const int gi = idx / nwords, wi = idx % nwords;
-            const int64_t widx = (int64_t)wbegin * WPC + wi;
+            const int64_t widx = (int64_t)wb * WPC + wi;
+            const int64_t G = (int64_t)tile_n * NG + gi;   // global 16-column group
             uint64_t m = 0;
-            if (widx < p.WA) {
-                if (gi < NG) {
-                    const int64_t G = (int64_t)tile_n * NG + gi;   // global 16-column group
-                    if (G * 16 < p.N) {
-                        if (p.bw == 16) {
-                            m = p.bt_bits[G * p.WA + widx];
-                        } else if (p.bw == 32) {
-                            m = p.bt_bits[(G >> 1) * p.WA + widx];
-                        } else {
-                            m = p.bt_bits[(2 * G) * p.WA + widx];
-                            if (2 * G + 1 < p.NB) m |= p.bt_bits[(2 * G + 1) * p.WA + widx];
-                        }
-                    }
+            if (widx < p.WA && G * 16 < p.N) {
+                if (p.bw == 16) {
+                    m = p.bt_bits[G * p.WA + widx];
+                } else if (p.bw == 32) {
+                    m = p.bt_bits[(G >> 1) * p.WA + widx];
                 } else {
-#pragma unroll
-                    for (int t = 0; t < TM / MMM_COLANY_ROWS; ++t) {
-                        const int64_t tt = row0 / MMM_COLANY_ROWS + t;
-                        if (tt < p.MT) m |= p.a_colany[tt * p.WA + widx];
-                    }
+                    m = p.bt_bits[(2 * G) * p.WA + widx];
+                    if (2 * G + 1 < p.NB) m |= p.bt_bits[(2 * G + 1) * p.WA + widx];
                 }
+                uint64_t any = 0;   // k whose column of A is zero in all rows of this tile are dropped
+#pragma unroll
+                for (int t = 0; t < RT * 16 / MMM_COLANY_ROWS; ++t) {
+                    const int64_t tt = row0 / MMM_COLANY_ROWS + t;
+                    if (tt < p.MT) any |= p.a_colany[tt * p.WA + widx];
+                }
+                m &= any;
             }
             mmm_dyn_words[idx] = m;
         }
+        for (int i = tid; i < p.window_chunks; i += NT)
+            cnt_lds[i] = wb + i < p.chunks_total ? p.a_cnt[(int64_t)tile_m * p.KBA + wb + i] : 0u;
     };
 
-    int wbegin = chunk_begin;   // first chunk of the current window
-    floatx4 areg[APT];
-    uint32_t anib[APT];
+    uint32_t nxt_val[EPT];
+    uint32_t cur_pos[EPT], nxt_pos[EPT];   // byte offset of the entry inside the slab
+    int cur_cnt = 0, nxt_cnt = 0;          // entries of the block, rounded up to whole wavefronts
     float bcur[GW][QB], bnext[GW][QB];
-    int cnt_cur[GW], cnt_next[GW];
+    int kcur[GW][QB], knext[GW][QB];       // listed k of the first batch of every group (kept from the B requests)
+    int cnt_cur[GW], cnt_next[GW], start_cur[GW], start_next[GW];
 
-    // request the A slab of chunk ci (relative) into registers
-    auto issue_a = [&](int ci) {
-        const int64_t k0 = (int64_t)(wbegin + ci) * KC;
+    // List entries of a block are dealt to the threads in rounds of ROUND; entry tid + j * NT is
+    // entry j of this thread.  The builder pads every list to a multiple of 64, so whether a
+    // wave has an entry j is a wave-uniform question.
+    const int wave_e0 = wave * 64;
+    // request the first round of list entries of step ci (relative to the window)
+    auto issue_entries = [&](int ci, uint32_t (&val)[EPT], uint32_t (&pos)[EPT], int &cnt) {
+        cnt = ((int)cnt_lds[ci] + 63) & ~63;
+        const uint2 *ent = p.a_ent + ((size_t)tile_m * p.KBA + wbegin + ci) * MMM_AB_CAP + tid;
+        // Loaded unconditionally (a round always lies inside the block's list area); what lies
+        // past the padded count is never used.  No branch, so nothing here waits for the data.
 #pragma unroll
-        for (int i = 0; i < APT; ++i) {
-            const int idx = tid + i * NT;
-            const int r = idx / C4, c4 = idx % C4;
-            const int64_t row = row0 + r, k = k0 + 4 * c4;
-            floatx4 v = {0.f, 0.f, 0.f, 0.f};
-            uint32_t nib = 0;
-            if (row < p.M && k < p.K) {
-                nib = (p.a_bytes[row * p.WA * 8 + (k >> 3)] >> (k & 4)) & 0xFu;
-                const T *src = X + row * p.ldx + k;
-                if (p.fast_x && k + 3 < p.K) {
-                    v = load4<T>(src);
-                } else {   // pad bits of the map are zero, so a set bit implies k+e < K
-                    if (nib & 1u) v.x = to_f32<T>(src[0]);
-                    if (nib & 2u) v.y = to_f32<T>(src[1]);
-                    if (nib & 4u) v.z = to_f32<T>(src[2]);
-                    if (nib & 8u) v.w = to_f32<T>(src[3]);
+        for (int j = 0; j < EPT; ++j) {
+            const uint2 e = ent[j * NT];
+            pos[j] = e.x;
+            val[j] = e.y;
+        }
+    };
+    auto scatter = [&](const uint32_t (&val)[EPT], const uint32_t (&pos)[EPT], int cnt) {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j)
+            if (wave_e0 + j * NT < cnt) *reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(As) + pos[j]) = val[j];
+    };
+    auto unscatter = [&](const uint32_t (&pos)[EPT], int cnt) {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j)
+            if (wave_e0 + j * NT < cnt) *reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(As) + pos[j]) = 0u;
+    };
+    // blocks with more entries than one round: the rest is fetched and scattered on the spot
+    auto scatter_rest = [&](int ci, int cnt) {
+        const uint2 *ent = p.a_ent + ((size_t)tile_m * p.KBA + wbegin + ci) * MMM_AB_CAP;
+        for (int e = ROUND + tid; e < cnt; e += NT) {
+            const uint2 v = ent[e];
+            *reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(As) + v.x) = v.y;
+        }
+    };
+    auto zero_slab = [&]() {
+        for (int r = tid / (KC / 4); r < TM; r += NT / (KC / 4))
+            *reinterpret_cast<floatx4 *>(&As[r * KCP + 4 * (tid % (KC / 4))]) = floatx4{0.f, 0.f, 0.f, 0.f};
+    };
+
+    // ---- k lists.  Once per window every wave turns the map words of its groups into compacted
+    // lists of live k: lane (g, w) owns word w of group g, a segmented prefix sum of the popcounts
+    // gives every word its place in the list of its group, and each lane then writes out the bit
+    // positions of its own word.  Entries are step-relative k (0..127); the entries of one step
+    // are contiguous, and `pref` (read with readlane) tells where each step starts.
+    constexpr int SEG = 64 / GW;          // lanes (= map words) per group: SEG / WPC steps per window
+    constexpr int REGION = SEG * 64;      // list bytes per group: the worst case
+    uint32_t pref = 0, incl = 0;          // exclusive / inclusive popcount prefix of this lane's word inside its group
+    auto build_lists = [&](int nchunks) {
+        const int g = lane / SEG, wi = lane % SEG;
+        uint64_t m = wi < nchunks * WPC ? mmm_dyn_words[(wave * GW + g) * nwords + wi] : 0ull;
+        const uint32_t cnt = (uint32_t)__popcll(m);
+        incl = cnt;
+#pragma unroll
+        for (int d = 1; d < SEG; d <<= 1) {
+            const uint32_t o = __shfl_up(incl, d, 64);
+            if (wi >= d) incl += o;
+        }
+        pref = incl - cnt;
+        uint8_t *dst = &lists[wave][g * REGION + pref];
+        const uint32_t half = (uint32_t)(wi % WPC) * 64u;
+        while (m != 0) {   // as many rounds as the fullest word of the wave has bits
+            *dst++ = (uint8_t)(half + (uint32_t)__ffsll((unsigned long long)m) - 1u);
+            m &= m - 1;
+        }
+    };
+    // first list slot and number of live k of step ci for group g
+    auto step_range = [&](int ci, int g, int &start, int &n) {
+        start = (int)__builtin_amdgcn_readlane(pref, g * SEG + ci * WPC);
+        n = (int)__builtin_amdgcn_readlane(incl, g * SEG + ci * WPC + WPC - 1) - start;
+    };
+
+    // B operands.  Every load is unconditional and in bounds: a slot past the end of the list
+    // re-reads the last listed row (its A operand is the zero column of the slab, so the product
+    // vanishes), and lanes past column N re-read column N-1 (their results are never written).
+    const int64_t col_base = ((int64_t)tile_n * NG + wave * GW) * 16 + c;   // column of this lane in its first group
+    int coff[GW];
+#pragma unroll
+    for (int g = 0; g < GW; ++g) coff[g] = (int)(min(col_base + g * 16, p.N - 1) - col_base);
+    auto load_b = [&](const T *Yc, int64_t k0, int kb, int g) -> float {
+        float v = to_f32<T>(Yc[(int)__umul24((uint32_t)kb, ldy32) + coff[g]]);
+        if (BW8) {   // a group spans two blocks: take only this lane's own block
+            const int64_t blk = (col_base + coff[g]) >> 3;
+            if (!((p.b_bits[(k0 + kb) * p.WB + (blk >> 6)] >> (blk & 63)) & 1ull)) v = 0.f;
+        }
+        return v;
+    };
+    // list slot t of a step with n live k: the listed k, clamped to the last one
+    auto list_k = [&](const uint8_t *lst, int t, int n) -> int { return lst[min(t, n - 1)]; };
+    auto issue_b_first = [&](int ci, const int (&start)[GW], const int (&cnt)[GW], float (&b)[GW][QB],
+                             int (&kk)[GW][QB]) {
+        const int64_t k0 = (int64_t)(wbegin + ci) * KC;
+        const T *Yc = Y + k0 * p.ldy + col_base;
+#pragma unroll
+        for (int g = 0; g < GW; ++g) {
+            if (cnt[g] > 0) {
+                const uint8_t *lst = &lists[wave][g * REGION + start[g]];
+#pragma unroll
+                for (int u = 0; u < QB; ++u) {
+                    kk[g][u] = list_k(lst, 4 * u + s, cnt[g]);
+                    b[g][u] = load_b(Yc, k0, kk[g][u], g);
                 }
             }
-            areg[i] = v;
-            anib[i] = nib;
-        }
-    };
-    // As[r][kk] = a_bits[row0+r, k0+kk] ? X[row0+r, k0+kk] : 0
-    auto store_a = [&]() {
-#pragma unroll
-        for (int i = 0; i < APT; ++i) {
-            const int idx = tid + i * NT;
-            const int r = idx / C4, c4 = idx % C4;
-            floatx4 v = areg[i];
-            const uint32_t nib = anib[i];
-            if (!(nib & 1u)) v.x = 0.f;
-            if (!(nib & 2u)) v.y = 0.f;
-            if (!(nib & 4u)) v.z = 0.f;
-            if (!(nib & 8u)) v.w = 0.f;
-            *reinterpret_cast<floatx4 *>(&As[r * KCP + 4 * c4]) = v;
-        }
-    };
-    // per 16-column group: compacted list of the live k of chunk ci (chunk-relative, ascending)
-    auto build_lists = [&](int ci, int buf, int (&cnt)[GW]) {
-#pragma unroll
-        for (int g = 0; g < GW; ++g) {
-            const int gi = wave * GW + g;
-            int base = 0;
-#pragma unroll
-            for (int wd = 0; wd < WPC; ++wd) {
-                const int wi = ci * WPC + wd;
-                const uint64_t m = uniform64(mmm_dyn_words[gi * nwords + wi] & mmm_dyn_words[NG * nwords + wi]);
-                const uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                if ((m >> lane) & 1ull) lists[buf][gi][base + pos] = (uint16_t)(wd * 64 + lane);
-                base += __popcll(m);
-            }
-            if (lane < LPAD) lists[buf][gi][base + lane] = (uint16_t)KC;
-            cnt[g] = base;
-        }
-    };
-    // one B operand: row k0+kk of Y at this lane's column, or 0 for a list sentinel
-    auto load_b = [&](int64_t k0, int kk, int64_t col, bool col_ok) -> float {
-        bool ok = col_ok && kk < KC;
-        if (p.bw == 8 && ok) {   // a group spans two blocks: take only this lane's own block
-            const int64_t blk = col >> 3;
-            ok = (p.b_bits[(k0 + kk) * p.WB + (blk >> 6)] >> (blk & 63)) & 1ull;
-        }
-        return ok ? to_f32<T>(Y[(k0 + kk) * p.ldy + col]) : 0.f;
-    };
-    auto issue_b_first = [&](int ci, int buf, float (&b)[GW][QB]) {
-        const int64_t k0 = (int64_t)(wbegin + ci) * KC;
-#pragma unroll
-        for (int g = 0; g < GW; ++g) {
-            const int gi = wave * GW + g;
-            const int64_t col = ((int64_t)tile_n * NG + gi) * 16 + c;
-#pragma unroll
-            for (int u = 0; u < QB; ++u) b[g][u] = load_b(k0, lists[buf][gi][4 * u + s], col, col < p.N);
         }
     };
 
-    // K range of this workgroup, in windows whose map words fit in LDS; inside a window the
-    // chunk loop is pipelined by one chunk
+    // K range of this workgroup, in windows of SEG / WPC steps; inside a window the step loop is
+    // pipelined by one step
     for (wbegin = chunk_begin; wbegin < chunk_end; wbegin += p.window_chunks) {
         const int nchunks = min(p.window_chunks, chunk_end - wbegin);
-        __syncthreads();   // previous window fully consumed (A slab and map words)
+        __syncthreads();   // previous window fully consumed; the slab is all zero
         load_words(wbegin);
         __syncthreads();
-        build_lists(0, 0, cnt_cur);
-        issue_a(0);
-        issue_b_first(0, 0, bcur);
-        store_a();
+        build_lists(nchunks);
+#pragma unroll
+        for (int g = 0; g < GW; ++g) step_range(0, g, start_cur[g], cnt_cur[g]);
+        issue_entries(0, nxt_val, cur_pos, cur_cnt);
+        issue_b_first(0, start_cur, cnt_cur, bcur, kcur);
+        scatter(nxt_val, cur_pos, cur_cnt);
+        if (cur_cnt > ROUND) scatter_rest(0, cur_cnt);
         __syncthreads();
 
-
         for (int ci = 0; ci < nchunks; ++ci) {
-            const int buf = ci & 1;
             const bool has_next = ci + 1 < nchunks;
             const int64_t k0 = (int64_t)(wbegin + ci) * KC;
+            const T *Yc = Y + k0 * p.ldy + col_base;
             if (has_next) {
-                build_lists(ci + 1, buf ^ 1, cnt_next);
-                issue_a(ci + 1);
-                issue_b_first(ci + 1, buf ^ 1, bnext);
+#pragma unroll
+                for (int g = 0; g < GW; ++g) step_range(ci + 1, g, start_next[g], cnt_next[g]);
+                issue_entries(ci + 1, nxt_val, nxt_pos, nxt_cnt);
+                issue_b_first(ci + 1, start_next, cnt_next, bnext, knext);
             }
 
-            // ---- multiply chunk ci: 4 listed k per MFMA
-    #pragma unroll
-            for (int g = 0; g < GW; ++g) {
-                const int n = cnt_cur[g];
-                const int gi = wave * GW + g;
-                const int64_t col = ((int64_t)tile_n * NG + gi) * 16 + c;
-                const bool col_ok = col < p.N;
-                const uint16_t *lst = lists[buf][gi];
-                float b[QB];
-    #pragma unroll
-                for (int u = 0; u < QB; ++u) b[u] = bcur[g][u];
-                for (int q = 0; q < n; q += LPAD) {
-                    float bn[QB];
-                    if (q + LPAD < n) {   // request the next batch of B operands before multiplying this one
-    #pragma unroll
-                        for (int u = 0; u < QB; ++u) bn[u] = load_b(k0, lst[q + LPAD + 4 * u + s], col, col_ok);
-                    } else {
-    #pragma unroll
-                        for (int u = 0; u < QB; ++u) bn[u] = 0.f;
-                    }
-                    int kk[QB];
-    #pragma unroll
-                    for (int u = 0; u < QB; ++u) kk[u] = lst[q + 4 * u + s];
-    #pragma unroll
+            // ---- multiply step ci: 4 listed k per MFMA.  First batch of every group: the listed
+            // k are already in registers, so all A operands are requested at once, then multiplied.
+            {
+                float a[GW][QB][RT];
+#pragma unroll
+                for (int g = 0; g < GW; ++g) {
+#pragma unroll
                     for (int u = 0; u < QB; ++u) {
-                        if (q + 4 * u < n) {
-    #pragma unroll
-                            for (int r = 0; r < RT; ++r) {
-                                const float a = As[(r * 16 + c) * KCP + kk[u]];
-                                acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[u], acc[g][r], 0, 0, 0);
-                            }
+                        const int kk = 4 * u + s < cnt_cur[g] ? kcur[g][u] : KC;   // KC: the zero column
+#pragma unroll
+                        for (int r = 0; r < RT; ++r) a[g][u][r] = As[c * KCP + kk + r * 16 * KCP];
+                    }
+                }
+#pragma unroll
+                for (int g = 0; g < GW; ++g) {
+#pragma unroll
+                    for (int u = 0; u < QB; ++u) {
+                        if (4 * u < cnt_cur[g]) {
+#pragma unroll
+                            for (int r = 0; r < RT; ++r)
+                                acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[g][u][r], bcur[g][u], acc[g][r], 0, 0, 0);
                         }
                     }
-    #pragma unroll
+                }
+            }
+            // further batches of long lists: B operands one batch ahead
+#pragma unroll
+            for (int g = 0; g < GW; ++g) {
+                const int n = cnt_cur[g];
+                if (n <= LPAD) continue;
+                const uint8_t *lst = &lists[wave][g * REGION + start_cur[g]];
+                float b[QB];
+#pragma unroll
+                for (int u = 0; u < QB; ++u) b[u] = load_b(Yc, k0, list_k(lst, LPAD + 4 * u + s, n), g);
+                for (int q = LPAD; q < n; q += LPAD) {
+                    float bn[QB];
+                    if (q + LPAD < n) {
+#pragma unroll
+                        for (int u = 0; u < QB; ++u) bn[u] = load_b(Yc, k0, list_k(lst, q + LPAD + 4 * u + s, n), g);
+                    } else {
+#pragma unroll
+                        for (int u = 0; u < QB; ++u) bn[u] = 0.f;
+                    }
+                    float a[QB][RT];
+#pragma unroll
+                    for (int u = 0; u < QB; ++u) {
+                        const int t = q + 4 * u + s;
+                        const int kk = t < n ? (int)lst[min(t, n - 1)] : KC;
+#pragma unroll
+                        for (int r = 0; r < RT; ++r) a[u][r] = As[c * KCP + kk + r * 16 * KCP];
+                    }
+#pragma unroll
+                    for (int u = 0; u < QB; ++u) {
+                        if (q + 4 * u < n) {
+#pragma unroll
+                            for (int r = 0; r < RT; ++r)
+                                acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][r], b[u], acc[g][r], 0, 0, 0);
+                        }
+                    }
+#pragma unroll
                     for (int u = 0; u < QB; ++u) b[u] = bn[u];
                 }
             }
 
-            __syncthreads();   // every wave is done reading the A slab of chunk ci
+            __syncthreads();   // every wave is done reading the slab of step ci
+            if (cur_cnt > ROUND)
+                zero_slab();
+            else
+                unscatter(cur_pos, cur_cnt);
             if (has_next) {
-                store_a();
-    #pragma unroll
+                __syncthreads();   // the slab is all zero
+                scatter(nxt_val, nxt_pos, nxt_cnt);
+                if (nxt_cnt > ROUND) scatter_rest(ci + 1, nxt_cnt);
+                cur_cnt = nxt_cnt;
+#pragma unroll
+                for (int j = 0; j < EPT; ++j) cur_pos[j] = nxt_pos[j];
+#pragma unroll
                 for (int g = 0; g < GW; ++g) {
                     cnt_cur[g] = cnt_next[g];
-    #pragma unroll
-                    for (int u = 0; u < QB; ++u) bcur[g][u] = bnext[g][u];
+                    start_cur[g] = start_next[g];
+#pragma unroll
+                    for (int u = 0; u < QB; ++u) {
+                        bcur[g][u] = bnext[g][u];
+                        kcur[g][u] = knext[g][u];
+                    }
                 }
             }
-            __syncthreads();   // the A slab of chunk ci+1 is complete
+            __syncthreads();   // the slab of step ci+1 is complete (or all zero after the last step)
         }
     }
 
@@ -368,24 +422,25 @@ typedef void (*matmul_kernel_fn)(const MatmulParams);
 
 struct VariantEntry {
     mmm_variant_info info;
-    matmul_kernel_fn f32, bf16;
+    matmul_kernel_fn f32, bf16, f32_bw8, bf16_bw8;
 };
 
-#define MMM_VARIANT(TM, GW, NW, KC)                                                                        \
-    {                                                                                                      \
-        {"TM" #TM "_TN" #GW "x" #NW "x16_KC" #KC, TM, 16 * GW * NW, KC, NW * 64, NW * GW},                 \
-            mmm_matmul_kernel<TM, GW, NW, KC, float>, mmm_matmul_kernel<TM, GW, NW, KC, uint16_t>          \
+#define MMM_VARIANT(RT, GW, NW)                                                                             \
+    {                                                                                                       \
+        {"R" #RT "x16_TN" #GW "x" #NW "x16", TM, 16 * GW * NW, KC, NW * 64, NW * GW, 16 * RT},                 \
+            mmm_matmul_kernel<RT, GW, NW, float, false>, mmm_matmul_kernel<RT, GW, NW, uint16_t, false>,     \
+            mmm_matmul_kernel<RT, GW, NW, float, true>, mmm_matmul_kernel<RT, GW, NW, uint16_t, true>        \
     }
 
 const VariantEntry g_variants[] = {
-    MMM_VARIANT(64, 4, 4, 128),    // 0: 64 x 256
-    MMM_VARIANT(64, 2, 4, 128),    // 1: 64 x 128
-    MMM_VARIANT(32, 4, 4, 128),    // 2: 32 x 256
-    MMM_VARIANT(32, 2, 4, 256),    // 3: 32 x 128, long chunk
-    MMM_VARIANT(128, 2, 4, 64),    // 4: 128 x 128, short chunk
-    MMM_VARIANT(64, 2, 4, 64),     // 5: 64 x 128, short chunk
-    MMM_VARIANT(64, 1, 8, 128),    // 6: 64 x 128, eight waves
-    MMM_VARIANT(32, 1, 4, 256),    // 7: 32 x 64
+    MMM_VARIANT(4, 2, 4),   // 0: 64 x 128
+    MMM_VARIANT(4, 4, 4),   // 1: 64 x 256
+    MMM_VARIANT(4, 1, 4),   // 2: 64 x 64
+    MMM_VARIANT(4, 1, 8),   // 3: 64 x 128, eight waves
+    MMM_VARIANT(4, 2, 8),   // 4: 64 x 256, eight waves
+    MMM_VARIANT(2, 2, 4),   // 5: 32 x 128   (matrices of at most 32 rows)
+    MMM_VARIANT(2, 4, 4),   // 6: 32 x 256
+    MMM_VARIANT(2, 1, 4),   // 7: 32 x 64
 };
 constexpr int32_t kVariants = (int32_t)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -397,17 +452,19 @@ const mmm_variant_info &mmm_variant(int32_t i) { return g_variants[i].info; }
 hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtype, const void *X, int64_t ldx,
                              const void *Y, int64_t ldy, float *C, int64_t ldc, int32_t accumulate, hipStream_t s)
 {
+    (void)X;   // the non-zero values of A travel inside the map (they were copied from X when it was built)
+    (void)ldx;
     if (pl.variant < 0 || pl.variant >= kVariants) return hipErrorInvalidValue;
     const VariantEntry &v = g_variants[pl.variant];
+    if (m->M > v.info.rows && v.info.rows < TM) return hipErrorInvalidValue;
     MatmulParams p{};
-    p.X = X;
-    p.ldx = ldx;
     p.Y = Y;
     p.ldy = ldy;
     p.C = C;
     p.ldc = ldc;
     p.P = m->partials;
-    p.a_bytes = reinterpret_cast<const uint8_t *>(m->a_bits);
+    p.a_cnt = m->a_cnt;
+    p.a_ent = reinterpret_cast<const uint2 *>(m->a_ent);
     p.a_colany = m->a_colany;
     p.b_bits = m->b_bits;
     p.bt_bits = m->bt_bits;
@@ -418,6 +475,7 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtyp
     p.WA = m->WA;
     p.WB = m->WB;
     p.MT = m->MT;
+    p.KBA = m->KBA;
     p.bw = m->bw;
     p.tiles_m = pl.tiles_m;
     p.tiles_n = pl.tiles_n;
@@ -425,18 +483,17 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtyp
     p.chunks_total = pl.chunks_total;
     p.chunks_per_split = pl.chunks_per_split;
     p.accumulate = accumulate;
-    const size_t esz = dtype == MMM_BF16 ? 2 : 4;
-    p.fast_x = ((reinterpret_cast<uintptr_t>(X) % (4 * esz)) == 0 && (ldx % 4) == 0) ? 1 : 0;
     if (pl.workgroups <= 0 || pl.workgroups > 0x7fffffffLL) return hipErrorInvalidValue;
     if (pl.split_k > 1 && (size_t)pl.split_k * (size_t)m->M * (size_t)m->N * sizeof(float) > m->partial_bytes)
         return hipErrorInvalidValue;
-    const int64_t wpc = v.info.KC / 64;
-    int64_t window = MMM_MAX_DYN_LDS / (int64_t)((v.info.groups + 1) * wpc * sizeof(uint64_t));
+    const int64_t per_chunk = (int64_t)v.info.groups * WPC * sizeof(uint64_t) + sizeof(uint32_t);
+    const int64_t gw = v.info.groups / (v.info.threads / 64);
+    int64_t window = 64 / (gw * WPC);   // one map word per lane: 64 words per wave and window
     if (window > pl.chunks_per_split) window = pl.chunks_per_split;
     if (window < 1) return hipErrorInvalidValue;
     p.window_chunks = (int32_t)window;
-    const size_t dyn = (size_t)(v.info.groups + 1) * (size_t)window * (size_t)wpc * sizeof(uint64_t);
-    matmul_kernel_fn fn = dtype == MMM_BF16 ? v.bf16 : v.f32;
+    const size_t dyn = (size_t)(window * per_chunk + 7) / 8 * 8;
+    matmul_kernel_fn fn = m->bw == 8 ? (dtype == MMM_BF16 ? v.bf16_bw8 : v.f32_bw8) : (dtype == MMM_BF16 ? v.bf16 : v.f32);
     (void)hipGetLastError();   // drop any stale error another library left on this thread
     hipLaunchKernelGGL(fn, dim3((uint32_t)pl.workgroups), dim3((uint32_t)v.info.threads), dyn, s, p);
     hipError_t e = hipGetLastError();
