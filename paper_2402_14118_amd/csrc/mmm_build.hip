@@ -18,10 +18,11 @@
 
 namespace {
 
-constexpr int BUILD_THREADS = 256;
-constexpr int A_ROWS_PER_WAVE = MMM_AB_ROWS / 4;       // 16
-constexpr int A_WORDS = MMM_AB_COLS / 64;              // 2
-constexpr int B_ROWS_PER_WAVE = MMM_BT_PIECE / 4;      // 4
+constexpr int BUILD_WAVES = 8;
+constexpr int BUILD_THREADS = BUILD_WAVES * 64;
+constexpr int A_ROWS_PER_WAVE = MMM_AB_ROWS / BUILD_WAVES;   // 8
+constexpr int A_WORDS = MMM_AB_COLS / 64;                    // 2
+constexpr int B_ROWS_PER_WAVE = MMM_BT_PIECE / BUILD_WAVES;  // 2
 
 struct BuildParams {
     const void *X;
@@ -78,7 +79,7 @@ __device__ __forceinline__ uint32_t mbcnt64(uint64_t m)
 }
 
 // ---- A side: one workgroup = one block of 64 rows x 128 columns ------------------------------
-// Wave w scans rows 16w..16w+15, one 64-column word per load.  Lane 2j+h of the wave ends up
+// Wave w scans rows 8w..8w+7, one 64-column word per load.  Lane 2j+h of the wave ends up
 // holding the bitmap word (row j, half h); entries are appended in (row, column) order.
 template <typename T>
 __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lane, int wave, uint64_t *red,
@@ -114,15 +115,15 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
     // bitmap words and per-wave entry offsets
     const bool have_word = lane < 2 * A_ROWS_PER_WAVE && rbase + (lane >> 1) < p.M && w_lo + (lane & 1) < p.WA;
     if (have_word) p.a_bits[(rbase + (lane >> 1)) * p.WA + w_lo + (lane & 1)] = mine;
-    const uint32_t my_cnt = (uint32_t)__popcll(mine);   // lanes >= 32 hold 0
+    const uint32_t my_cnt = (uint32_t)__popcll(mine);   // lanes past the wave's words hold 0
     uint32_t incl = my_cnt;
 #pragma unroll
-    for (int d = 1; d < 32; d <<= 1) {
+    for (int d = 1; d < 2 * A_ROWS_PER_WAVE; d <<= 1) {
         const uint32_t o = __shfl_up(incl, d, 64);
         if (lane >= d) incl += o;
     }
     const uint32_t excl = incl - my_cnt;
-    if (lane == 31) tot[wave] = incl;
+    if (lane == 2 * A_ROWS_PER_WAVE - 1) tot[wave] = incl;
     if (lane == 0) {
         red[wave * A_WORDS + 0] = colany[0];
         red[wave * A_WORDS + 1] = colany[1];
@@ -130,12 +131,18 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
     __syncthreads();
     uint32_t base = 0;
     for (int w = 0; w < wave; ++w) base += tot[w];
-    if (threadIdx.x == 0) p.a_cnt[b] = tot[0] + tot[1] + tot[2] + tot[3];
+    uint32_t total = 0;
+    for (int w = 0; w < BUILD_WAVES; ++w) total += tot[w];
+    if (threadIdx.x == 0) p.a_cnt[b] = total;
     if (threadIdx.x < 2 * A_WORDS) {   // column-any words of the two 32-row tiles of this block
         const int t = threadIdx.x >> 1, h = threadIdx.x & 1;
         const int64_t tile = bi * (MMM_AB_ROWS / MMM_COLANY_ROWS) + t;
         if (tile < p.MT && w_lo + h < p.WA)
-            p.a_colany[tile * p.WA + w_lo + h] = red[(2 * t) * A_WORDS + h] | red[(2 * t + 1) * A_WORDS + h];
+        {
+            uint64_t any = 0;   // waves t*W/2 .. (t+1)*W/2-1 cover the 32 rows of tile t
+            for (int w = t * (BUILD_WAVES / 2); w < (t + 1) * (BUILD_WAVES / 2); ++w) any |= red[w * A_WORDS + h];
+            p.a_colany[tile * p.WA + w_lo + h] = any;
+        }
     }
     // compacted entries {byte offset inside the multiplier's LDS slab, value}, in (row, column) order
     uint2 *ent = p.a_ent + (size_t)b * MMM_AB_CAP;
@@ -155,8 +162,7 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
         }
     }
     // pad the list to a whole number of wavefronts with entries that write 0 to a spare slab cell
-    if (wave == 3) {
-        const uint32_t total = base + tot[3];
+    if (wave == BUILD_WAVES - 1) {
         const uint32_t e = total + lane;
         if (e < ((total + 63u) & ~63u)) ent[e] = make_uint2((uint32_t)MMM_AB_COLS * 4u, 0u);
     }
@@ -210,7 +216,8 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
     pieces[wave * 64 + lane] = piece_bits;
     __syncthreads();
     if (wave == 0) {
-        const uint32_t v = pieces[lane] | pieces[64 + lane] | pieces[128 + lane] | pieces[192 + lane];
+        uint32_t v = 0;
+        for (int w = 0; w < BUILD_WAVES; ++w) v |= pieces[w * 64 + lane];
         const int64_t blk = w * 64 + lane;
         if (blk < p.NB) p.bt16[blk * (p.WA * 4) + piece] = (uint16_t)v;
     }
@@ -219,9 +226,9 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
 template <typename T>
 __global__ __launch_bounds__(BUILD_THREADS) void mmm_build_kernel(const BuildParams p)
 {
-    __shared__ uint64_t red[4 * A_WORDS];
-    __shared__ uint32_t tot[4];
-    __shared__ uint32_t pieces[4 * 64];
+    __shared__ uint64_t red[BUILD_WAVES * A_WORDS];
+    __shared__ uint32_t tot[BUILD_WAVES];
+    __shared__ uint32_t pieces[BUILD_WAVES * 64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t b = blockIdx.x;

@@ -17,7 +17,7 @@ constexpr int MMM_AB_ROWS = 64;
 constexpr int MMM_AB_COLS = 128;
 constexpr int MMM_AB_CAP = MMM_AB_ROWS * MMM_AB_COLS;   // list capacity per block: the worst case
 // Row pitch (floats) of the LDS slab a block is scattered into; cell (0, MMM_AB_COLS) is spare.
-constexpr int MMM_SLAB_LD = MMM_AB_COLS + 4;
+constexpr int MMM_SLAB_LD = MMM_AB_COLS + 1;   // odd pitch: the 16 rows of an MFMA operand fall into 16 different LDS banks
 // Dynamic LDS the masked GEMM may use for map words (static use stays below 44 KiB).
 constexpr int MMM_MAX_DYN_LDS = 20 * 1024;
 

@@ -35,7 +35,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int TM = MMM_AB_ROWS;   // rows of C per workgroup = rows of a block of A
 constexpr int KC = MMM_AB_COLS;   // k per step = columns of a block of A
-constexpr int KCP = KC + 4;       // padded LDS row; columns KC..KC+3 stay zero (k-list sentinel)
+constexpr int KCP = MMM_SLAB_LD;  // LDS row pitch; column KC stays zero (the A operand of a k-list slot past the end)
 constexpr int WPC = KC / 64;      // map words per step
 constexpr int QB = 4;             // k-list quads per batch
 constexpr int LPAD = 4 * QB;
@@ -148,51 +148,64 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
             cnt_lds[i] = wb + i < p.chunks_total ? p.a_cnt[(int64_t)tile_m * p.KBA + wb + i] : 0u;
     };
 
-    uint32_t nxt_val[EPT];
-    uint32_t cur_pos[EPT], nxt_pos[EPT];   // byte offset of the entry inside the slab
-    int cur_cnt = 0, nxt_cnt = 0;          // entries of the block, rounded up to whole wavefronts
-    float bcur[GW][QB], bnext[GW][QB];
-    int kcur[GW][QB], knext[GW][QB];       // listed k of the first batch of every group (kept from the B requests)
-    int cnt_cur[GW], cnt_next[GW], start_cur[GW], start_next[GW];
+    // One round of a block's non-zero list, in registers: entry tid + j * NT is entry j of this
+    // thread.  The builder pads every list to a multiple of 64, so whether a wave has an entry j
+    // is a wave-uniform question.
+    struct Entries {
+        uint32_t pos[EPT];   // byte offset inside the slab
+        uint32_t val[EPT];   // float bit pattern
+        int cnt;             // entries of the block, rounded up to whole wavefronts
+    };
+    // First batch of B operands of one step, per group of this wave.
+    struct BFirst {
+        float b[GW][QB];
+        int kk[GW][QB];      // the listed k they belong to
+        int cnt[GW], start[GW];
+    };
+    Entries ecur, eP, eQ;
+    BFirst bP, bQ;
+    ecur.cnt = 0;
 
-    // List entries of a block are dealt to the threads in rounds of ROUND; entry tid + j * NT is
-    // entry j of this thread.  The builder pads every list to a multiple of 64, so whether a
-    // wave has an entry j is a wave-uniform question.
     const int wave_e0 = wave * 64;
+    char *slab = reinterpret_cast<char *>(As);
     // request the first round of list entries of step ci (relative to the window)
-    auto issue_entries = [&](int ci, uint32_t (&val)[EPT], uint32_t (&pos)[EPT], int &cnt) {
-        cnt = ((int)cnt_lds[ci] + 63) & ~63;
+    auto issue_entries = [&](int ci, Entries &e) {
+        e.cnt = ((int)cnt_lds[ci] + 63) & ~63;
         const uint2 *ent = p.a_ent + ((size_t)tile_m * p.KBA + wbegin + ci) * MMM_AB_CAP + tid;
         // Loaded unconditionally (a round always lies inside the block's list area); what lies
         // past the padded count is never used.  No branch, so nothing here waits for the data.
 #pragma unroll
         for (int j = 0; j < EPT; ++j) {
-            const uint2 e = ent[j * NT];
-            pos[j] = e.x;
-            val[j] = e.y;
+            const uint2 v = ent[j * NT];
+            e.pos[j] = v.x;
+            e.val[j] = v.y;
         }
     };
-    auto scatter = [&](const uint32_t (&val)[EPT], const uint32_t (&pos)[EPT], int cnt) {
-#pragma unroll
-        for (int j = 0; j < EPT; ++j)
-            if (wave_e0 + j * NT < cnt) *reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(As) + pos[j]) = val[j];
+    // The slab is filled and emptied with integer adds on the float bit patterns: a cell goes
+    // 0 -> bits -> 0 exactly, whatever the order in which the adds of different threads land, so
+    // emptying step c and filling step c+1 need no barrier between them.
+    auto slab_add = [&](uint32_t pos, uint32_t v) {
+        __hip_atomic_fetch_add(reinterpret_cast<uint32_t *>(slab + pos), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     };
-    auto unscatter = [&](const uint32_t (&pos)[EPT], int cnt) {
-#pragma unroll
-        for (int j = 0; j < EPT; ++j)
-            if (wave_e0 + j * NT < cnt) *reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(As) + pos[j]) = 0u;
-    };
-    // blocks with more entries than one round: the rest is fetched and scattered on the spot
-    auto scatter_rest = [&](int ci, int cnt) {
+    // blocks with more entries than one round: the rest is fetched and applied on the spot
+    auto apply_rest = [&](int ci, int cnt, bool fill) {
         const uint2 *ent = p.a_ent + ((size_t)tile_m * p.KBA + wbegin + ci) * MMM_AB_CAP;
         for (int e = ROUND + tid; e < cnt; e += NT) {
             const uint2 v = ent[e];
-            *reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(As) + v.x) = v.y;
+            slab_add(v.x, fill ? v.y : 0u - v.y);
         }
     };
-    auto zero_slab = [&]() {
-        for (int r = tid / (KC / 4); r < TM; r += NT / (KC / 4))
-            *reinterpret_cast<floatx4 *>(&As[r * KCP + 4 * (tid % (KC / 4))]) = floatx4{0.f, 0.f, 0.f, 0.f};
+    auto fill_slab = [&](int ci, const Entries &e) {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j)
+            if (wave_e0 + j * NT < e.cnt) slab_add(e.pos[j], e.val[j]);
+        if (e.cnt > ROUND) apply_rest(ci, e.cnt, true);
+    };
+    auto empty_slab = [&](int ci, const Entries &e) {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j)
+            if (wave_e0 + j * NT < e.cnt) slab_add(e.pos[j], 0u - e.val[j]);
+        if (e.cnt > ROUND) apply_rest(ci, e.cnt, false);
     };
 
     // ---- k lists.  Once per window every wave turns the map words of its groups into compacted
@@ -244,138 +257,125 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     };
     // list slot t of a step with n live k: the listed k, clamped to the last one
     auto list_k = [&](const uint8_t *lst, int t, int n) -> int { return lst[min(t, n - 1)]; };
-    auto issue_b_first = [&](int ci, const int (&start)[GW], const int (&cnt)[GW], float (&b)[GW][QB],
-                             int (&kk)[GW][QB]) {
+    auto issue_b_first = [&](int ci, BFirst &f) {
         const int64_t k0 = (int64_t)(wbegin + ci) * KC;
         const T *Yc = Y + k0 * p.ldy + col_base;
 #pragma unroll
         for (int g = 0; g < GW; ++g) {
-            if (cnt[g] > 0) {
-                const uint8_t *lst = &lists[wave][g * REGION + start[g]];
+            step_range(ci, g, f.start[g], f.cnt[g]);
+            if (f.cnt[g] > 0) {
+                const uint8_t *lst = &lists[wave][g * REGION + f.start[g]];
 #pragma unroll
                 for (int u = 0; u < QB; ++u) {
-                    kk[g][u] = list_k(lst, 4 * u + s, cnt[g]);
-                    b[g][u] = load_b(Yc, k0, kk[g][u], g);
+                    f.kk[g][u] = list_k(lst, 4 * u + s, f.cnt[g]);
+                    f.b[g][u] = load_b(Yc, k0, f.kk[g][u], g);
                 }
             }
         }
     };
 
-    // K range of this workgroup, in windows of SEG / WPC steps; inside a window the step loop is
-    // pipelined by one step
+    // ---- multiply step ci: 4 listed k per MFMA
+    auto multiply = [&](int ci, const BFirst &f) {
+        const int64_t k0 = (int64_t)(wbegin + ci) * KC;
+        const T *Yc = Y + k0 * p.ldy + col_base;
+        // First batch of every group: the listed k are already in registers, so all A operands
+        // are requested at once, then multiplied.
+        {
+            float a[GW][QB][RT];
+#pragma unroll
+            for (int g = 0; g < GW; ++g) {
+#pragma unroll
+                for (int u = 0; u < QB; ++u) {
+                    if (4 * u < f.cnt[g]) {
+                        const int kk = 4 * u + s < f.cnt[g] ? f.kk[g][u] : KC;   // KC: the zero column
+#pragma unroll
+                        for (int r = 0; r < RT; ++r) a[g][u][r] = As[c * KCP + kk + r * 16 * KCP];
+                    }
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < GW; ++g) {
+#pragma unroll
+                for (int u = 0; u < QB; ++u) {
+                    if (4 * u < f.cnt[g]) {
+#pragma unroll
+                        for (int r = 0; r < RT; ++r)
+                            acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[g][u][r], f.b[g][u], acc[g][r], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        // further batches of long lists: B operands one batch ahead
+#pragma unroll
+        for (int g = 0; g < GW; ++g) {
+            const int n = f.cnt[g];
+            if (n <= LPAD) continue;
+            const uint8_t *lst = &lists[wave][g * REGION + f.start[g]];
+            float b[QB];
+#pragma unroll
+            for (int u = 0; u < QB; ++u) b[u] = load_b(Yc, k0, list_k(lst, LPAD + 4 * u + s, n), g);
+            for (int q = LPAD; q < n; q += LPAD) {
+                float bn[QB];
+                if (q + LPAD < n) {
+#pragma unroll
+                    for (int u = 0; u < QB; ++u) bn[u] = load_b(Yc, k0, list_k(lst, q + LPAD + 4 * u + s, n), g);
+                } else {
+#pragma unroll
+                    for (int u = 0; u < QB; ++u) bn[u] = 0.f;
+                }
+                float a[QB][RT];
+#pragma unroll
+                for (int u = 0; u < QB; ++u) {
+                    const int t = q + 4 * u + s;
+                    const int kk = t < n ? (int)lst[min(t, n - 1)] : KC;
+#pragma unroll
+                    for (int r = 0; r < RT; ++r) a[u][r] = As[c * KCP + kk + r * 16 * KCP];
+                }
+#pragma unroll
+                for (int u = 0; u < QB; ++u) {
+                    if (q + 4 * u < n) {
+#pragma unroll
+                        for (int r = 0; r < RT; ++r)
+                            acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][r], b[u], acc[g][r], 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < QB; ++u) b[u] = bn[u];
+            }
+        }
+    };
+
+    // One step.  On entry the slab holds block ci; `have` holds the list of block ci+1 (requested
+    // a step ago), `load` is free and receives the request for block ci+2; likewise the B
+    // operands of step ci are in `use` and those of step ci+1 are requested into `next`.
+    auto do_step = [&](int ci, int nchunks, Entries &have, Entries &load, const BFirst &use, BFirst &next) {
+        if (ci + 2 < nchunks) issue_entries(ci + 2, load);
+        if (ci + 1 < nchunks) issue_b_first(ci + 1, next);
+        multiply(ci, use);
+        __syncthreads();   // every wave is done reading the slab of step ci
+        empty_slab(ci, ecur);
+        if (ci + 1 < nchunks) {
+            fill_slab(ci + 1, have);
+            ecur = have;
+        }
+        __syncthreads();   // the slab holds block ci+1 (or is all zero after the last step)
+    };
+
+    // K range of this workgroup, in windows of SEG / WPC steps
     for (wbegin = chunk_begin; wbegin < chunk_end; wbegin += p.window_chunks) {
         const int nchunks = min(p.window_chunks, chunk_end - wbegin);
         __syncthreads();   // previous window fully consumed; the slab is all zero
         load_words(wbegin);
         __syncthreads();
         build_lists(nchunks);
-#pragma unroll
-        for (int g = 0; g < GW; ++g) step_range(0, g, start_cur[g], cnt_cur[g]);
-        issue_entries(0, nxt_val, cur_pos, cur_cnt);
-        issue_b_first(0, start_cur, cnt_cur, bcur, kcur);
-        scatter(nxt_val, cur_pos, cur_cnt);
-        if (cur_cnt > ROUND) scatter_rest(0, cur_cnt);
+        issue_entries(0, ecur);
+        if (nchunks > 1) issue_entries(1, eP);
+        issue_b_first(0, bP);
+        fill_slab(0, ecur);
         __syncthreads();
-
-        for (int ci = 0; ci < nchunks; ++ci) {
-            const bool has_next = ci + 1 < nchunks;
-            const int64_t k0 = (int64_t)(wbegin + ci) * KC;
-            const T *Yc = Y + k0 * p.ldy + col_base;
-            if (has_next) {
-#pragma unroll
-                for (int g = 0; g < GW; ++g) step_range(ci + 1, g, start_next[g], cnt_next[g]);
-                issue_entries(ci + 1, nxt_val, nxt_pos, nxt_cnt);
-                issue_b_first(ci + 1, start_next, cnt_next, bnext, knext);
-            }
-
-            // ---- multiply step ci: 4 listed k per MFMA.  First batch of every group: the listed
-            // k are already in registers, so all A operands are requested at once, then multiplied.
-            {
-                float a[GW][QB][RT];
-#pragma unroll
-                for (int g = 0; g < GW; ++g) {
-#pragma unroll
-                    for (int u = 0; u < QB; ++u) {
-                        const int kk = 4 * u + s < cnt_cur[g] ? kcur[g][u] : KC;   // KC: the zero column
-#pragma unroll
-                        for (int r = 0; r < RT; ++r) a[g][u][r] = As[c * KCP + kk + r * 16 * KCP];
-                    }
-                }
-#pragma unroll
-                for (int g = 0; g < GW; ++g) {
-#pragma unroll
-                    for (int u = 0; u < QB; ++u) {
-                        if (4 * u < cnt_cur[g]) {
-#pragma unroll
-                            for (int r = 0; r < RT; ++r)
-                                acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[g][u][r], bcur[g][u], acc[g][r], 0, 0, 0);
-                        }
-                    }
-                }
-            }
-            // further batches of long lists: B operands one batch ahead
-#pragma unroll
-            for (int g = 0; g < GW; ++g) {
-                const int n = cnt_cur[g];
-                if (n <= LPAD) continue;
-                const uint8_t *lst = &lists[wave][g * REGION + start_cur[g]];
-                float b[QB];
-#pragma unroll
-                for (int u = 0; u < QB; ++u) b[u] = load_b(Yc, k0, list_k(lst, LPAD + 4 * u + s, n), g);
-                for (int q = LPAD; q < n; q += LPAD) {
-                    float bn[QB];
-                    if (q + LPAD < n) {
-#pragma unroll
-                        for (int u = 0; u < QB; ++u) bn[u] = load_b(Yc, k0, list_k(lst, q + LPAD + 4 * u + s, n), g);
-                    } else {
-#pragma unroll
-                        for (int u = 0; u < QB; ++u) bn[u] = 0.f;
-                    }
-                    float a[QB][RT];
-#pragma unroll
-                    for (int u = 0; u < QB; ++u) {
-                        const int t = q + 4 * u + s;
-                        const int kk = t < n ? (int)lst[min(t, n - 1)] : KC;
-#pragma unroll
-                        for (int r = 0; r < RT; ++r) a[u][r] = As[c * KCP + kk + r * 16 * KCP];
-                    }
-#pragma unroll
-                    for (int u = 0; u < QB; ++u) {
-                        if (q + 4 * u < n) {
-#pragma unroll
-                            for (int r = 0; r < RT; ++r)
-                                acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][r], b[u], acc[g][r], 0, 0, 0);
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < QB; ++u) b[u] = bn[u];
-                }
-            }
-
-            __syncthreads();   // every wave is done reading the slab of step ci
-            if (cur_cnt > ROUND)
-                zero_slab();
-            else
-                unscatter(cur_pos, cur_cnt);
-            if (has_next) {
-                __syncthreads();   // the slab is all zero
-                scatter(nxt_val, nxt_pos, nxt_cnt);
-                if (nxt_cnt > ROUND) scatter_rest(ci + 1, nxt_cnt);
-                cur_cnt = nxt_cnt;
-#pragma unroll
-                for (int j = 0; j < EPT; ++j) cur_pos[j] = nxt_pos[j];
-#pragma unroll
-                for (int g = 0; g < GW; ++g) {
-                    cnt_cur[g] = cnt_next[g];
-                    start_cur[g] = start_next[g];
-#pragma unroll
-                    for (int u = 0; u < QB; ++u) {
-                        bcur[g][u] = bnext[g][u];
-                        kcur[g][u] = knext[g][u];
-                    }
-                }
-            }
-            __syncthreads();   // the slab of step ci+1 is complete (or all zero after the last step)
+        for (int ci = 0; ci < nchunks; ci += 2) {
+            do_step(ci, nchunks, eP, eQ, bP, bQ);
+            if (ci + 1 < nchunks) do_step(ci + 1, nchunks, eQ, eP, bQ, bP);
         }
     }
 
