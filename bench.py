@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--split-k", type=int, default=0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 64 MiB device copy a few times, so that a counter run "
+                         "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards without communication, "
@@ -89,6 +92,12 @@ def main():
         build()
         matmul()
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     # timed region: exactly `steps` steps; per-kernel durations from events on the launch stream
     K = args.steps
@@ -113,33 +122,46 @@ def main():
     dense_flops = 2.0 * w.M * w.K * w.N
     value = useful_flops / (ms_per_step * 1e-3) / 1e9
 
-    # algorithmic bytes of one launch (what the method itself must move)
+    # algorithmic bytes of one launch: what the method itself must move ("Roofline")
     WA, NB = (w.K + 63) // 64, w.N // w.bw
     WB = (NB + 63) // 64
-    map_bytes = w.M * WA * 8 + ((w.M + 31) // 32) * WA * 8 + w.K * WB * 8 + NB * WA * 8
-    kept_blocks = occ_b if w.keep_blocks is None and w.keep_rows is None else None
-    if kept_blocks is None:     # blocks the keep bitmaps leave switched on are the ones the builder must read
-        kb = np.ones((w.K, NB), dtype=bool)
-        if w.keep_rows is not None:
-            kb &= synth.unpack_bits(w.keep_rows.reshape(1, -1), w.K)[0][:, None]
-        if w.keep_blocks is not None:
-            kb &= synth.unpack_bits(w.keep_blocks, NB)
-        kept_blocks = int(kb.sum())
-    build_bytes = w.M * w.K * esz + kept_blocks * w.bw * esz + map_bytes
-    matmul_bytes = w.M * w.K * esz + occ_b * w.bw * esz + map_bytes + w.M * w.N * 4
+    a_bits_b, colany_b = w.M * WA * 8, ((w.M + 31) // 32) * WA * 8
+    b_bits_b, bt_b = w.K * WB * 8, NB * WA * 8
+    a_blocks = ((w.M + 63) // 64) * ((w.K + 127) // 128)
+    a_list_b = nnz_a * 8 + a_blocks * 4            # {slab offset, value} per non-zero, one count per block
+    kb = np.ones((w.K, NB), dtype=bool)             # blocks the keep bitmaps leave switched on: the builder must read them
+    if w.keep_rows is not None:
+        kb &= synth.unpack_bits(w.keep_rows.reshape(1, -1), w.K)[0][:, None]
+    if w.keep_blocks is not None:
+        kb &= synth.unpack_bits(w.keep_blocks, NB)
+    kept_blocks = int(kb.sum())
+    keep_in_b = (a_bits_b if w.keep_a is not None else 0) + (b_bits_b if w.keep_blocks is not None else 0) \
+        + (WA * 8 if w.keep_rows is not None else 0)
+    build_bytes = w.M * w.K * esz + kept_blocks * w.bw * esz + keep_in_b \
+        + a_bits_b + colany_b + a_list_b + b_bits_b + bt_b
+    matmul_bytes = a_list_b + occ_b * w.bw * esz + colany_b + bt_b + w.M * w.N * 4
     dominant = "mmm_matmul_kernel" if t_matmul >= t_build else "mmm_build_kernel"
     dom_ms = max(t_matmul, t_build)
     dom_bytes = matmul_bytes if t_matmul >= t_build else build_bytes
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    traffic = None                                   # HBM bytes per launch from rocprofv3 --pmc runs, if recorded
+    tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.txt")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == dominant:
+                traffic = float(f[2])
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "algorithmic_bytes": dom_bytes, "avg_launch_us": dom_ms * 1e3,
                 "build": {"avg_launch_us": t_build * 1e3, "algorithmic_bytes": build_bytes,
                           "achieved_GBs": build_bytes / (t_build * 1e-3) / 1e9},
                 "matmul": {"avg_launch_us": t_matmul * 1e3, "algorithmic_bytes": matmul_bytes,
                            "achieved_GBs": matmul_bytes / (t_matmul * 1e-3) / 1e9,
                            "useful_TFLOPs": useful_flops / (t_matmul * 1e-3) / 1e12,
-                           "useful_frac_of_fp32_vector_peak": useful_flops / (t_matmul * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS}}
+                           "useful_frac_of_fp32_vector_peak": useful_flops / (t_matmul * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
+                           "mfma_TFLOPs_issued": 2.0 * w.M * occ_b * w.bw / (t_matmul * 1e-3) / 1e12,
+                           "mfma_frac_of_fp32_matrix_peak": 2.0 * w.M * occ_b * w.bw / (t_matmul * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS}}
 
     out = {
         "metric": "useful_gflops", "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": K,

@@ -99,7 +99,7 @@ mmm_plan make_plan(const mmm_maps *m, int32_t dt)
     int64_t split = g_opt_split.load();
     if (split <= 0) {
         split = 1;
-        if (tiles < 512) split = (1024 + tiles - 1) / tiles;   // aim at ~4 workgroups per CU
+        if (tiles < 256) split = (512 + tiles - 1) / tiles;   // fewer tiles than CUs: split K to give every CU work
     }
     const int64_t max_by_ws = (int64_t)(m->partial_bytes / ((size_t)m->M * (size_t)m->N * sizeof(float)));
     if (split > max_by_ws) split = max_by_ws;

@@ -379,24 +379,53 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
         }
     }
 
-    // ---- write C (or this split's partial sums): every element exactly once
-    // accumulator layout of the 16x16x4 MFMA: lane holds rows 4*s + v (v = 0..3) of column c
+    // ---- write C (or this split's partial sums): every element exactly once.
+    // Accumulator layout of the 16x16x4 MFMA: lane holds rows 4*s + v (v = 0..3) of column c.
+    // Each wave first lays its 16*RT x 16*GW tile out row-major in its own piece of the (now
+    // free) slab, then stores whole rows with 16-byte lanes, so full cache lines leave the CU.
+    float *out = p.split_k > 1 ? p.P + (int64_t)split * p.M * p.N : p.C;
+    const int64_t ldo = p.split_k > 1 ? p.N : p.ldc;
+    const bool add = p.split_k == 1 && p.accumulate;
+    const int64_t wcol0 = ((int64_t)tile_n * NG + wave * GW) * 16;   // first column of this wave
+    constexpr int WCOLS = 16 * GW;
+    constexpr bool FITS = NW * RT * 16 * WCOLS <= TM * KCP;
+    const bool vec_ok = FITS && (reinterpret_cast<uintptr_t>(out) % 16 == 0) && (ldo % 4 == 0) && wcol0 + WCOLS <= p.N;
+    if (vec_ok) {
+        float *mine = As + wave * (RT * 16 * WCOLS);
 #pragma unroll
-    for (int g = 0; g < GW; ++g) {
-        const int64_t col = ((int64_t)tile_n * NG + wave * GW + g) * 16 + c;
-        if (col >= p.N) continue;
+        for (int g = 0; g < GW; ++g)
 #pragma unroll
-        for (int r = 0; r < RT; ++r) {
+            for (int r = 0; r < RT; ++r)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int64_t row = row0 + r * 16 + s * 4 + v;
-                if (row >= p.M) continue;
-                const float val = acc[g][r][v];
-                if (p.split_k > 1) {
-                    p.P[((int64_t)split * p.M + row) * p.N + col] = val;
-                } else {
-                    float *dst = p.C + row * p.ldc + col;
-                    *dst = p.accumulate ? *dst + val : val;
+                for (int v = 0; v < 4; ++v) mine[(r * 16 + s * 4 + v) * WCOLS + g * 16 + c] = acc[g][r][v];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        constexpr int V4 = WCOLS / 4;                  // 16-byte pieces per row
+        constexpr int ROWS_PER_PASS = 64 / V4;
+#pragma unroll
+        for (int pass = 0; pass < RT * 16 / ROWS_PER_PASS; ++pass) {
+            const int rr = pass * ROWS_PER_PASS + lane / V4, c4 = lane % V4;
+            const int64_t row = row0 + rr;
+            if (row < p.M) {
+                floatx4 val = *reinterpret_cast<const floatx4 *>(&mine[rr * WCOLS + 4 * c4]);
+                floatx4 *dst = reinterpret_cast<floatx4 *>(out + row * ldo + wcol0 + 4 * c4);
+                if (add) val += *dst;
+                *dst = val;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < GW; ++g) {
+            const int64_t col = wcol0 + g * 16 + c;
+            if (col >= p.N) continue;
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int64_t row = row0 + r * 16 + s * 4 + v;
+                    if (row >= p.M) continue;
+                    float *dst = out + row * ldo + col;
+                    *dst = add ? *dst + acc[g][r][v] : acc[g][r][v];
                 }
             }
         }
