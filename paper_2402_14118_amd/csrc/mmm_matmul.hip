@@ -39,7 +39,7 @@ constexpr int KCP = MMM_SLAB_LD;  // LDS row pitch; column KC stays zero (the A 
 constexpr int WPC = KC / 64;      // map words per step
 constexpr int QB = 4;             // k-list quads per batch
 constexpr int LPAD = 4 * QB;
-constexpr int EPT = 8;            // list entries of A per thread and round
+
 
 struct MatmulParams {
     const void *Y;
@@ -84,6 +84,7 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
 {
     constexpr int NG = NW * GW;
     constexpr int NT = NW * 64;
+    constexpr int EPT = 1024 / NT;    // list entries of A per thread and round
     constexpr int ROUND = NT * EPT;   // list entries one round of the workgroup moves
 
     __shared__ __align__(16) float As[TM * KCP];
