@@ -122,7 +122,7 @@ def main():
     dense_flops = 2.0 * w.M * w.K * w.N
     value = useful_flops / (ms_per_step * 1e-3) / 1e9
 
-    # algorithmic bytes of one launch: what the method itself must move ("Roofline")
+    # algorithmic bytes of one launch: what the method itself must move (lists, occupied blocks, maps, C)
     WA, NB = (w.K + 63) // 64, w.N // w.bw
     WB = (NB + 63) // 64
     a_bits_b, colany_b = w.M * WA * 8, ((w.M + 31) // 32) * WA * 8

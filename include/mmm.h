@@ -105,8 +105,11 @@ void mmm_maps_release(mmm_maps *maps);
  * sparse row preprocessing" for A -- here both become bitmaps):
  *     a_bits[i,k]  = pred(X[i,k]) & keep_bits[i,k] & (X[i,k] != 0)
  *     b_bits[k,jb] = keep_rows[k] & keep_blocks[k,jb] & (some Y[k, jb*bw .. jb*bw+bw) != 0)
- * plus derived forms the multiplication reads (column-any words of A per 32-row
- * tile, the B map transposed to one bit-row per block column).
+ * plus derived forms the multiplication reads: column-any words of A per 32-row
+ * tile, the B map transposed to one bit-row per block column, and, for every
+ * 64 x 128 block of A, the count and a compacted list of its non-zero elements
+ * with their values (the count-and-offsets form of Fig. "Blocked sparse row
+ * preprocessing", with the value stored beside the offset).
  * Either side may be skipped by passing X == NULL (then ma is ignored) or
  * Y == NULL: that side's maps from an earlier call are kept -- the B side of a
  * weight matrix is built once and reused (section 3: rows of B are preprocessed
@@ -134,6 +137,20 @@ mmm_status mmm_maps_view(const mmm_maps *maps, const uint64_t **a_bits, int64_t 
 mmm_status mmm_maps_view_derived(const mmm_maps *maps, const uint64_t **a_colany, const uint64_t **bt_bits,
                                  int64_t *k_words);
 
+/* Device pointers to the blocked non-zero lists of A, for inspection.  A is cut
+ * into *blocks_m x *blocks_k blocks of 64 rows x 128 columns (ragged at the far
+ * edges); block (bm, bk) has index bm * *blocks_k + bk.
+ *   counts [block]            : number of non-zero elements of A in the block
+ *   entries[block][*capacity] : the first counts[block] words describe those
+ *       elements, each exactly once, in an order that is fixed for a given A:
+ *       low 32 bits  = 4 * (129 * row_in_block + column_in_block)
+ *       high 32 bits = the value as IEEE float bits (bf16 widened)
+ *     then words {4 * 128, 0} up to the next multiple of 64 (none if the count
+ *     is one already); words beyond that are unspecified.
+ * Errors: MMM_ERR_INVALID_ARG. */
+mmm_status mmm_maps_view_lists(const mmm_maps *maps, const uint32_t **counts, const uint64_t **entries,
+                               int64_t *blocks_m, int64_t *blocks_k, int64_t *capacity);
+
 /* Counts taken from the maps (runs a small reduction on `hip_stream`, then
  * WAITS for the stream): non-zeros of A, occupied blocks of B, and useful
  * multiply-adds  sum_k nnz(A[:,k]) * bw * occupied(B[k,:])  -- the products the
@@ -146,8 +163,11 @@ mmm_status mmm_maps_stats(const mmm_maps *maps, uint64_t *nnz_a, uint64_t *occup
 /* C = A x B (accumulate == 0) or C += A x B (accumulate != 0) using the maps:
  *     C[i,j] (+)= sum over k with a_bits[i,k] & b_bits[k, j div bw] of X[i,k] * Y[k,j]
  * (paper, section 3 "Matrix Multiplication", Fig. "MMM Pseudocode").  X and Y
- * must hold the same values the maps were built from.  Every element of C is
- * written exactly once, zeros included.  float accumulation; the result is
+ * must hold the same values the maps were built from: the values of A are taken
+ * from the lists mmm_build_maps wrote (X is checked like any argument but not
+ * read again), those of B from Y.  Products the maps skip contribute exactly 0,
+ * whatever the skipped operands hold; kept operands are assumed finite.  Every
+ * element of C is written exactly once, zeros included.  float accumulation; the result is
  * bitwise reproducible from run to run for the same inputs and shape.
  * Errors: MMM_ERR_INVALID_ARG, MMM_ERR_SHAPE, MMM_ERR_DTYPE,
  * MMM_ERR_MAPS_MISMATCH (a side not built, or dt differs from the build),

@@ -26,7 +26,7 @@ MMM_PRED_NONZERO, MMM_PRED_GT, MMM_PRED_ABS_GT = 0, 1, 2
 
 EXPORTS = [
     "mmm_maps_workspace_bytes", "mmm_maps_init", "mmm_maps_release", "mmm_build_maps", "mmm_maps_view",
-    "mmm_maps_view_derived", "mmm_maps_stats", "mmm_matmul", "mmm_set_option", "mmm_matmul_variant_count",
+    "mmm_maps_view_derived", "mmm_maps_view_lists", "mmm_maps_stats", "mmm_matmul", "mmm_set_option", "mmm_matmul_variant_count",
     "mmm_matmul_variant_name", "mmm_matmul_plan", "mmm_status_string", "mmm_last_device_error",
 ]
 
@@ -61,6 +61,7 @@ def _load() -> ctypes.CDLL:
     lib.mmm_build_maps.argtypes = [vp, i32, vp, i64, c.POINTER(MaskA), vp, i64, c.POINTER(MaskB), vp]
     lib.mmm_maps_view.argtypes = [vp, c.POINTER(vp), c.POINTER(i64), c.POINTER(vp), c.POINTER(i64)]
     lib.mmm_maps_view_derived.argtypes = [vp, c.POINTER(vp), c.POINTER(vp), c.POINTER(i64)]
+    lib.mmm_maps_view_lists.argtypes = [vp, c.POINTER(vp), c.POINTER(vp), c.POINTER(i64), c.POINTER(i64), c.POINTER(i64)]
     lib.mmm_maps_stats.argtypes = [vp, c.POINTER(c.c_uint64), c.POINTER(c.c_uint64), c.POINTER(c.c_uint64), vp]
     lib.mmm_matmul.argtypes = [vp, i32, vp, i64, vp, i64, vp, i64, i32, vp]
     lib.mmm_set_option.argtypes = [c.c_char_p, i64]
@@ -147,6 +148,15 @@ def mmm_maps_view_derived(maps: int):
     kw = ctypes.c_int64(0)
     _check(lib.mmm_maps_view_derived(maps, ctypes.byref(a), ctypes.byref(b), ctypes.byref(kw)), "mmm_maps_view_derived")
     return a.value, b.value, kw.value
+
+
+def mmm_maps_view_lists(maps: int):
+    """(counts address, entries address, blocks_m, blocks_k, capacity)"""
+    a, b = ctypes.c_void_p(None), ctypes.c_void_p(None)
+    bm, bk, cap = ctypes.c_int64(0), ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib.mmm_maps_view_lists(maps, ctypes.byref(a), ctypes.byref(b), ctypes.byref(bm), ctypes.byref(bk),
+                                   ctypes.byref(cap)), "mmm_maps_view_lists")
+    return a.value, b.value, bm.value, bk.value, cap.value
 
 
 def mmm_maps_stats(maps: int, stream=None):

@@ -248,6 +248,18 @@ mmm_status mmm_maps_view_derived(const mmm_maps *maps, const uint64_t **a_colany
     return MMM_OK;
 }
 
+mmm_status mmm_maps_view_lists(const mmm_maps *maps, const uint32_t **counts, const uint64_t **entries,
+                               int64_t *blocks_m, int64_t *blocks_k, int64_t *capacity)
+{
+    if (maps == nullptr) return MMM_ERR_INVALID_ARG;
+    if (counts) *counts = maps->a_cnt;
+    if (entries) *entries = maps->a_ent;
+    if (blocks_m) *blocks_m = maps->MBA;
+    if (blocks_k) *blocks_k = maps->KBA;
+    if (capacity) *capacity = MMM_AB_CAP;
+    return MMM_OK;
+}
+
 mmm_status mmm_maps_stats(const mmm_maps *maps, uint64_t *nnz_a, uint64_t *occupied_blocks_b,
                           uint64_t *useful_macs, void *hip_stream)
 {

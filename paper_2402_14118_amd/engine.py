@@ -75,3 +75,13 @@ class MaskedMatmul:
     def bt_bits(self) -> torch.Tensor:
         _, b, kw = B.mmm_maps_view_derived(self.maps)
         return self._bits_tensor(b, self.N // self.bw, kw)
+
+    def a_lists(self):
+        """(counts int32 [blocks_m, blocks_k], entries int64 [blocks_m * blocks_k, capacity]) as views of the workspace."""
+        c, e, bm, bk, cap = B.mmm_maps_view_lists(self.maps)
+        base = self.workspace.data_ptr()
+        assert 0 <= c - base and c - base + bm * bk * 4 <= self.workspace.numel()
+        assert 0 <= e - base and e - base + bm * bk * cap * 8 <= self.workspace.numel()
+        counts = self.workspace[c - base: c - base + bm * bk * 4].view(torch.int32).view(bm, bk)
+        entries = self.workspace[e - base: e - base + bm * bk * cap * 8].view(torch.int64).view(bm * bk, cap)
+        return counts, entries

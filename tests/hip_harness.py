@@ -64,6 +64,14 @@ class HipRun:
         torch.cuda.synchronize()
         return (self.eng.a_colany().cpu().numpy().view(np.uint64), self.eng.bt_bits().cpu().numpy().view(np.uint64))
 
+    def lists_host(self):
+        """(counts [blocks_m, blocks_k], list of per-block uint64 entry arrays up to the padded count)"""
+        torch.cuda.synchronize()
+        counts, entries = self.eng.a_lists()
+        counts = counts.cpu().numpy()
+        padded = (counts.reshape(-1).astype(np.int64) + 63) // 64 * 64
+        return counts, [entries[b, : int(n)].cpu().numpy().view(np.uint64) for b, n in enumerate(padded)]
+
 
 def assert_close(C, C_ref, mag, dtype, what=""):
     err = np.abs(C.astype(np.float64) - C_ref.astype(np.float64))

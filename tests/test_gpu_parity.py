@@ -33,6 +33,26 @@ def derived_from_bits(ab, bb, M, K, NB):
     return colany, bt
 
 
+def check_lists(run, ab, w, what):
+    """The blocked non-zero lists of A against the oracle's bitmap and the input values: per 64 x 128 block the
+    same set of {slab offset, value bits} words (their order is the library's own), then the stated padding."""
+    counts, ents = run.lists_host()
+    keep = synth.unpack_bits(ab, w.K)
+    xbits = np.ascontiguousarray(w.X, dtype=np.float32).view(np.uint32)
+    MB, KB = (w.M + 63) // 64, (w.K + 127) // 128
+    assert counts.shape == (MB, KB), what
+    for bm in range(MB):
+        for bk in range(KB):
+            kp = keep[bm * 64:(bm + 1) * 64, bk * 128:(bk + 1) * 128]
+            r, c = np.nonzero(kp)
+            want = (xbits[bm * 64 + r, bk * 128 + c].astype(np.uint64) << np.uint64(32)) | (4 * (129 * r + c)).astype(np.uint64)
+            got = ents[bm * KB + bk]
+            n = int(counts[bm, bk])
+            assert n == len(want), f"{what}: block ({bm},{bk}) count {n} want {len(want)}"
+            np.testing.assert_array_equal(np.sort(got[:n]), np.sort(want), err_msg=f"{what}: block ({bm},{bk}) entries")
+            assert (got[n:] == np.uint64(4 * 128)).all(), f"{what}: block ({bm},{bk}) padding"
+
+
 def check_workload(w, what, exact=False, **ld):
     print(f"case {what}: M={w.M} K={w.K} N={w.N} bw={w.bw} dtype={w.dtype}", flush=True)
     ab, bb, C_ref, mag = oracle.run_workload(w)
@@ -44,6 +64,8 @@ def check_workload(w, what, exact=False, **ld):
     exp_colany, exp_bt = derived_from_bits(ab, bb, w.M, w.K, w.N // w.bw)
     np.testing.assert_array_equal(colany, exp_colany, err_msg=f"{what}: a_colany")
     np.testing.assert_array_equal(bt, exp_bt, err_msg=f"{what}: bt_bits")
+    if w.M * w.K <= 1 << 22:
+        check_lists(run, ab, w, what)
     assert run.eng.stats() == oracle.counts(ab, bb, w.M, w.K, w.N, w.bw), what
     if exact:
         np.testing.assert_array_equal(C, C_ref, err_msg=what)
