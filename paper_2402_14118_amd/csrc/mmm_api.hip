@@ -81,13 +81,14 @@ mmm_plan make_plan(const mmm_maps *m, int32_t dt)
     if (v >= 0 && v < mmm_variant_count() && mmm_variant((int32_t)v).rows < MMM_AB_ROWS && m->M > mmm_variant((int32_t)v).rows)
         v = -1;   // that kernel computes too few rows for this matrix
     if (v < 0 || v >= mmm_variant_count()) {
-        // automatic: 32-row kernels for short matrices; otherwise the column tile that still
-        // gives every CU several workgroups
+        // automatic: the shapes that put sixteen waves on a compute unit.  32-row kernel for short
+        // matrices; otherwise the 256-column tile (one workgroup of sixteen waves per CU) when that
+        // still gives every CU a workgroup, else the 128-column tile (two workgroups of eight waves)
         if (m->M <= 32) {
-            v = 5;
+            v = 9;
         } else {
-            const int64_t t128 = ((m->M + 63) / 64) * ((m->N + 127) / 128);
-            v = t128 >= 4096 ? 1 : 0;
+            const int64_t t256 = ((m->M + 63) / 64) * ((m->N + 255) / 256);
+            v = t256 >= 256 ? 8 : 3;
         }
     }
     const mmm_variant_info &vi = mmm_variant((int32_t)v);

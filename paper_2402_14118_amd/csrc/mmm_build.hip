@@ -156,7 +156,7 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
             if (m == 0) continue;
             const uint32_t off = base + __builtin_amdgcn_readlane(excl, 2 * j + h);
             if ((m >> lane) & 1ull) {
-                const uint32_t slab = (uint32_t)((wave * A_ROWS_PER_WAVE + j) * MMM_SLAB_LD + 64 * h + lane) * 4u;
+                const uint32_t slab = mmm_slab_pos((uint32_t)(wave * A_ROWS_PER_WAVE + j), (uint32_t)(64 * h + lane));
                 ent[off + mbcnt64(m)] = make_uint2(slab, u[j][h]);
             }
         }
@@ -164,7 +164,7 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
     // pad the list to a whole number of wavefronts with entries that write 0 to a spare slab cell
     if (wave == BUILD_WAVES - 1) {
         const uint32_t e = total + lane;
-        if (e < ((total + 63u) & ~63u)) ent[e] = make_uint2((uint32_t)MMM_AB_COLS * 4u, 0u);
+        if (e < ((total + 63u) & ~63u)) ent[e] = make_uint2(MMM_SLAB_SPARE, 0u);
     }
 }
 

@@ -16,8 +16,18 @@ constexpr int MMM_BT_PIECE = 16;
 constexpr int MMM_AB_ROWS = 64;
 constexpr int MMM_AB_COLS = 128;
 constexpr int MMM_AB_CAP = MMM_AB_ROWS * MMM_AB_COLS;   // list capacity per block: the worst case
-// Row pitch (floats) of the LDS slab a block is scattered into; cell (0, MMM_AB_COLS) is spare.
-constexpr int MMM_SLAB_LD = MMM_AB_COLS + 1;   // odd pitch: the 16 rows of an MFMA operand fall into 16 different LDS banks
+// The LDS slab a block is scattered into is column-major with the rows r, r+16, r+32, r+48 of a
+// column next to each other: one 16-byte read yields the A operands of all four 16-row MFMA tiles
+// for one k, and the 16 lanes of an operand read 256 contiguous bytes.  Inside its column the
+// 16-byte cell of row r sits at slot (r + column) mod 16, so that neighbouring columns of one row
+// (neighbours in a block's list) fall into different LDS banks.  Column MMM_AB_COLS is spare and
+// always zero.
+constexpr int MMM_SLAB_FLOATS = (MMM_AB_COLS + 1) * MMM_AB_ROWS;
+__host__ __device__ constexpr uint32_t mmm_slab_pos(uint32_t row, uint32_t col)   // byte offset of element (row, col)
+{
+    return ((col * 16u + ((row + col) & 15u)) * 4u + (row >> 4)) * 4u;
+}
+constexpr uint32_t MMM_SLAB_SPARE = mmm_slab_pos(0, MMM_AB_COLS);
 // Dynamic LDS the masked GEMM may use for map words (static use stays below 44 KiB).
 constexpr int MMM_MAX_DYN_LDS = 20 * 1024;
 
@@ -33,7 +43,7 @@ struct mmm_maps {
     uint64_t *a_bits;
     uint64_t *a_colany;
     uint32_t *a_cnt;   // [MBA][KBA] non-zeros per block
-    uint64_t *a_ent;   // [MBA*KBA][MMM_AB_CAP] entries {byte offset row * MMM_SLAB_LD + column in the slab, value bits},
+    uint64_t *a_ent;   // [MBA*KBA][MMM_AB_CAP] entries {byte offset mmm_slab_pos(row, column) in the slab, value bits},
                        // padded to a multiple of 64 with {spare cell, 0}
     uint64_t *b_bits;
     uint64_t *bt_bits;

@@ -16,17 +16,21 @@
 // only the non-zero elements of A travel.  The map builder lists, per block of
 // 64 rows x 128 columns, the count of non-zeros with their offsets and values
 // (the blocked sparse row structure of section 3, "Optimizations").  A
-// workgroup owns 64 rows of C; per 128-wide step of k it scatters that block's
-// list into a zeroed LDS slab, which all of its waves then read as the dense
-// 16 x 4 MFMA operand; afterwards it zeroes the same positions again.  Columns
-// of the slab that are zero for all 64 rows are dropped from the k lists
-// (column-any words).
+// workgroup owns 64 rows of C and keeps two LDS slabs.  While the waves multiply
+// step c out of one slab (reading it as the dense 16 x 4 MFMA operand), they
+// take the list of block c-1 out of the other slab and put the list of block
+// c+1 into it, both with integer adds on the float bit patterns, which commute:
+// one barrier per step.  Columns of a block that are zero in all its rows are
+// dropped from the k lists (column-any words).
 //
-// Pipeline: while step c is multiplied, the list entries of step c+1 are in
-// flight into registers, the k lists of step c+1 are built, and its first B
-// operands are in flight too; inside a k list the B operands of the next batch
-// are requested before the current batch is multiplied.  The map words and
-// block counts a workgroup needs are copied to LDS in windows of many steps.
+// Pipeline: list entries travel into registers two steps before they are
+// added, the first B operands of a step are requested one step ahead, and inside
+// a long k list the B operands of the next batch are requested before the
+// current batch is multiplied.  The map words a workgroup needs are copied to
+// LDS, and expanded to k lists, in windows of several steps.  The kernel is
+// bound by instruction issue and latency rather than by any pipe, so the
+// workgroup shapes that do best are those that put sixteen waves on a compute
+// unit (eight or sixteen waves per workgroup, one 16-column group per wave).
 #include "mmm_internal.h"
 
 namespace {
@@ -35,9 +39,8 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int TM = MMM_AB_ROWS;   // rows of C per workgroup = rows of a block of A
 constexpr int KC = MMM_AB_COLS;   // k per step = columns of a block of A
-constexpr int KCP = MMM_SLAB_LD;  // LDS row pitch; column KC stays zero (the A operand of a k-list slot past the end)
 constexpr int WPC = KC / 64;      // map words per step
-constexpr int QB = 4;             // k-list quads per batch
+constexpr int QB = 6;             // k-list quads per batch
 constexpr int LPAD = 4 * QB;
 
 
@@ -55,7 +58,8 @@ struct MatmulParams {
     int64_t M, K, N, NB, WA, WB, MT, KBA;
     int32_t bw;
     int32_t tiles_m, tiles_n, split_k, chunks_total, chunks_per_split;
-    int32_t window_chunks;   // steps whose map words and counts are held in LDS at a time
+    int32_t window_chunks;   // steps whose map words are held in LDS (and whose k lists exist) at a time
+    int32_t zero;            // always 0
     int32_t accumulate;
 };
 
@@ -73,9 +77,12 @@ __device__ __forceinline__ uint32_t xcd_contiguous_id(uint32_t b, uint32_t n)
     return x * q + (x < rem ? x : rem) + i;
 }
 
-// [NG][nwords] 64-bit words (per group: transposed-B word AND column-any word of A),
-// followed by window_chunks 32-bit block counts
+// [NG][nwords] 64-bit words (per group: transposed-B word AND column-any word of A)
 extern __shared__ uint64_t mmm_dyn_words[];
+
+// map words one wave expands into k lists per window (fewer for the eight-wave workgroups, whose
+// lists would otherwise keep a second workgroup off the compute unit)
+constexpr int list_words(int nw) { return nw >= 8 ? 16 : 32; }
 
 // RT  16-row MFMA sub-tiles computed (4: all 64 rows of the block; 2: matrices of at most 32 rows)
 // GW  16-column groups per wave, NW waves per workgroup: TN = 16*GW*NW columns
@@ -86,9 +93,13 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     constexpr int NT = NW * 64;
     constexpr int EPT = 1024 / NT;    // list entries of A per thread and round
     constexpr int ROUND = NT * EPT;   // list entries one round of the workgroup moves
+    constexpr int SLAB = MMM_SLAB_FLOATS;   // floats per slab; column KC stays zero (the A operand of a k-list slot past the end)
+    constexpr int LW = list_words(NW);
+    constexpr int SEG = LW / GW;      // lanes (= map words) per group: SEG / WPC steps per window
+    constexpr int REGION = SEG * 64;  // list bytes per group: the worst case
 
-    __shared__ __align__(16) float As[TM * KCP];
-    __shared__ uint8_t lists[NW][64 * 64 + 4];   // per wave: k lists of its groups for one window
+    __shared__ __align__(16) float As[2 * SLAB];       // two slabs: one is multiplied from while the other changes
+    __shared__ uint8_t lists[NW][GW * REGION + 4];     // per wave: k lists of its groups for one window
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -103,7 +114,6 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     const int chunk_begin = split * p.chunks_per_split;
     const int chunk_end = min(chunk_begin + p.chunks_per_split, p.chunks_total);
     const int nwords = p.window_chunks * WPC;
-    uint32_t *cnt_lds = reinterpret_cast<uint32_t *>(mmm_dyn_words + NG * nwords);
 
     const T *Y = static_cast<const T *>(p.Y);
     const uint32_t ldy32 = (uint32_t)p.ldy;
@@ -114,12 +124,13 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
 #pragma unroll
         for (int r = 0; r < RT; ++r) acc[g][r] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // the slab starts out all zero and every step leaves it all zero again
-    for (int i = tid; i < TM * KCP / 4; i += NT) reinterpret_cast<floatx4 *>(As)[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // both slabs start out all zero; whatever is added to a slab is subtracted again later
+    for (int i = tid; i < 2 * SLAB / 4; i += NT) reinterpret_cast<floatx4 *>(As)[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     int wbegin = chunk_begin;   // first step of the current window
+    int wchunks = 0;            // steps in the current window
 
-    // map words and block counts of the steps [wb, wb + window_chunks) -> LDS
+    // map words of the steps [wb, wb + window_chunks) -> LDS
     auto load_words = [&](int wb) {
         for (int idx = tid; idx < NG * nwords; idx += NT) {
             const int gi = idx / nwords, wi = idx % nwords;
@@ -145,17 +156,15 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
             }
             mmm_dyn_words[idx] = m;
         }
-        for (int i = tid; i < p.window_chunks; i += NT)
-            cnt_lds[i] = wb + i < p.chunks_total ? p.a_cnt[(int64_t)tile_m * p.KBA + wb + i] : 0u;
     };
 
     // One round of a block's non-zero list, in registers: entry tid + j * NT is entry j of this
     // thread.  The builder pads every list to a multiple of 64, so whether a wave has an entry j
     // is a wave-uniform question.
     struct Entries {
-        uint32_t pos[EPT];   // byte offset inside the slab
+        uint32_t pos[EPT];   // byte offset inside a slab
         uint32_t val[EPT];   // float bit pattern
-        int cnt;             // entries of the block, rounded up to whole wavefronts
+        uint32_t cntv;       // entries of the block (the same value in every lane); 0: no block
     };
     // First batch of B operands of one step, per group of this wave.
     struct BFirst {
@@ -163,16 +172,18 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
         int kk[GW][QB];      // the listed k they belong to
         int cnt[GW], start[GW];
     };
-    Entries ecur, eP, eQ;
-    BFirst bP, bQ;
-    ecur.cnt = 0;
+    Entries eprev, ecur, enext, eload;
+    BFirst buse, bnext;
+    eprev.cntv = ecur.cntv = enext.cntv = eload.cntv = 0;
 
     const int wave_e0 = wave * 64;
-    char *slab = reinterpret_cast<char *>(As);
-    // request the first round of list entries of step ci (relative to the window)
-    auto issue_entries = [&](int ci, Entries &e) {
-        e.cnt = ((int)cnt_lds[ci] + 63) & ~63;
-        const uint2 *ent = p.a_ent + ((size_t)tile_m * p.KBA + wbegin + ci) * MMM_AB_CAP + tid;
+    // request the first round of the list of block ch (and its count) into registers
+    auto issue_entries = [&](int ch, Entries &e) {
+        const size_t blk = (size_t)tile_m * p.KBA + ch;
+        // the count comes through the vector memory path like the entries, so that it arrives in
+        // order with them (the lane term is always 0)
+        e.cntv = p.a_cnt[blk + (size_t)(lane & p.zero)];
+        const uint2 *ent = p.a_ent + blk * MMM_AB_CAP + tid;
         // Loaded unconditionally (a round always lies inside the block's list area); what lies
         // past the padded count is never used.  No branch, so nothing here waits for the data.
 #pragma unroll
@@ -182,31 +193,28 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
             e.val[j] = v.y;
         }
     };
-    // The slab is filled and emptied with integer adds on the float bit patterns: a cell goes
+    auto padded_count = [&](const Entries &e) -> int {
+        return ((int)__builtin_amdgcn_readfirstlane(e.cntv) + 63) & ~63;
+    };
+    // A slab is filled and emptied with integer adds on the float bit patterns: a cell goes
     // 0 -> bits -> 0 exactly, whatever the order in which the adds of different threads land, so
-    // emptying step c and filling step c+1 need no barrier between them.
-    auto slab_add = [&](uint32_t pos, uint32_t v) {
+    // removing block c-1 from a slab and putting block c+1 into it need no barrier between them.
+    auto slab_add = [&](char *slab, uint32_t pos, uint32_t v) {
         __hip_atomic_fetch_add(reinterpret_cast<uint32_t *>(slab + pos), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     };
+    // the first round of a list, from registers
+    auto apply_round = [&](char *slab, const Entries &e, int cnt, bool fill) {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j)
+            if (wave_e0 + j * NT < cnt) slab_add(slab, e.pos[j], fill ? e.val[j] : 0u - e.val[j]);
+    };
     // blocks with more entries than one round: the rest is fetched and applied on the spot
-    auto apply_rest = [&](int ci, int cnt, bool fill) {
-        const uint2 *ent = p.a_ent + ((size_t)tile_m * p.KBA + wbegin + ci) * MMM_AB_CAP;
+    auto apply_rest = [&](char *slab, int ch, int cnt, bool fill) {
+        const uint2 *ent = p.a_ent + ((size_t)tile_m * p.KBA + ch) * MMM_AB_CAP;
         for (int e = ROUND + tid; e < cnt; e += NT) {
             const uint2 v = ent[e];
-            slab_add(v.x, fill ? v.y : 0u - v.y);
+            slab_add(slab, v.x, fill ? v.y : 0u - v.y);
         }
-    };
-    auto fill_slab = [&](int ci, const Entries &e) {
-#pragma unroll
-        for (int j = 0; j < EPT; ++j)
-            if (wave_e0 + j * NT < e.cnt) slab_add(e.pos[j], e.val[j]);
-        if (e.cnt > ROUND) apply_rest(ci, e.cnt, true);
-    };
-    auto empty_slab = [&](int ci, const Entries &e) {
-#pragma unroll
-        for (int j = 0; j < EPT; ++j)
-            if (wave_e0 + j * NT < e.cnt) slab_add(e.pos[j], 0u - e.val[j]);
-        if (e.cnt > ROUND) apply_rest(ci, e.cnt, false);
     };
 
     // ---- k lists.  Once per window every wave turns the map words of its groups into compacted
@@ -214,12 +222,10 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     // gives every word its place in the list of its group, and each lane then writes out the bit
     // positions of its own word.  Entries are step-relative k (0..127); the entries of one step
     // are contiguous, and `pref` (read with readlane) tells where each step starts.
-    constexpr int SEG = 64 / GW;          // lanes (= map words) per group: SEG / WPC steps per window
-    constexpr int REGION = SEG * 64;      // list bytes per group: the worst case
     uint32_t pref = 0, incl = 0;          // exclusive / inclusive popcount prefix of this lane's word inside its group
     auto build_lists = [&](int nchunks) {
-        const int g = lane / SEG, wi = lane % SEG;
-        uint64_t m = wi < nchunks * WPC ? mmm_dyn_words[(wave * GW + g) * nwords + wi] : 0ull;
+        const int g = (lane / SEG) % GW, wi = lane % SEG;
+        uint64_t m = (lane < LW && wi < nchunks * WPC) ? mmm_dyn_words[(wave * GW + g) * nwords + wi] : 0ull;
         const uint32_t cnt = (uint32_t)__popcll(m);
         incl = cnt;
 #pragma unroll
@@ -275,8 +281,9 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
         }
     };
 
-    // ---- multiply step ci: 4 listed k per MFMA
-    auto multiply = [&](int ci, const BFirst &f) {
+    // ---- multiply step ci from slab S: 4 listed k per MFMA.  `between` runs after the first A
+    // operands have been requested and before the first MFMA.
+    auto multiply = [&](int ci, const BFirst &f, const float *S, auto &&between) {
         const int64_t k0 = (int64_t)(wbegin + ci) * KC;
         const T *Yc = Y + k0 * p.ldy + col_base;
         // First batch of every group: the listed k are already in registers, so all A operands
@@ -290,10 +297,11 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
                     if (4 * u < f.cnt[g]) {
                         const int kk = 4 * u + s < f.cnt[g] ? f.kk[g][u] : KC;   // KC: the zero column
 #pragma unroll
-                        for (int r = 0; r < RT; ++r) a[g][u][r] = As[c * KCP + kk + r * 16 * KCP];
+                        for (int r = 0; r < RT; ++r) a[g][u][r] = S[kk * 64 + ((c + kk) & 15) * 4 + r];
                     }
                 }
             }
+            between();
 #pragma unroll
             for (int g = 0; g < GW; ++g) {
 #pragma unroll
@@ -330,7 +338,7 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
                     const int t = q + 4 * u + s;
                     const int kk = t < n ? (int)lst[min(t, n - 1)] : KC;
 #pragma unroll
-                    for (int r = 0; r < RT; ++r) a[u][r] = As[c * KCP + kk + r * 16 * KCP];
+                    for (int r = 0; r < RT; ++r) a[u][r] = S[kk * 64 + ((c + kk) & 15) * 4 + r];
                 }
 #pragma unroll
                 for (int u = 0; u < QB; ++u) {
@@ -346,39 +354,54 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
         }
     };
 
-    // One step.  On entry the slab holds block ci; `have` holds the list of block ci+1 (requested
-    // a step ago), `load` is free and receives the request for block ci+2; likewise the B
-    // operands of step ci are in `use` and those of step ci+1 are requested into `next`.
-    auto do_step = [&](int ci, int nchunks, Entries &have, Entries &load, const BFirst &use, BFirst &next) {
-        if (ci + 2 < nchunks) issue_entries(ci + 2, load);
-        if (ci + 1 < nchunks) issue_b_first(ci + 1, next);
-        multiply(ci, use);
-        __syncthreads();   // every wave is done reading the slab of step ci
-        empty_slab(ci, ecur);
-        if (ci + 1 < nchunks) {
-            fill_slab(ci + 1, have);
-            ecur = have;
-        }
-        __syncthreads();   // the slab holds block ci+1 (or is all zero after the last step)
+    // start of a window: map words -> LDS -> k lists, and the first B operands of its first step
+    auto open_window = [&](int wb) {
+        wbegin = wb;
+        wchunks = min(p.window_chunks, chunk_end - wb);
+        load_words(wb);
+        __syncthreads();
+        build_lists(wchunks);
+        issue_b_first(0, buse);
     };
 
-    // K range of this workgroup, in windows of SEG / WPC steps
-    for (wbegin = chunk_begin; wbegin < chunk_end; wbegin += p.window_chunks) {
-        const int nchunks = min(p.window_chunks, chunk_end - wbegin);
-        __syncthreads();   // previous window fully consumed; the slab is all zero
-        load_words(wbegin);
-        __syncthreads();
-        build_lists(nchunks);
-        issue_entries(0, ecur);
-        if (nchunks > 1) issue_entries(1, eP);
-        issue_b_first(0, bP);
-        fill_slab(0, ecur);
-        __syncthreads();
-        for (int ci = 0; ci < nchunks; ci += 2) {
-            do_step(ci, nchunks, eP, eQ, bP, bQ);
-            if (ci + 1 < nchunks) do_step(ci + 1, nchunks, eQ, eP, bQ, bP);
+    if (chunk_begin < chunk_end) {
+        issue_entries(chunk_begin, ecur);
+        if (chunk_begin + 1 < chunk_end) issue_entries(chunk_begin + 1, enext);
+        open_window(chunk_begin);   // its barrier also makes the zeroed slabs visible
+        {
+            const int cnt = padded_count(ecur);
+            apply_round(reinterpret_cast<char *>(As), ecur, cnt, true);
+            if (cnt > ROUND) apply_rest(reinterpret_cast<char *>(As), chunk_begin, cnt, true);
         }
     }
+    // Step ch multiplies from slab (ch - chunk_begin) & 1, which holds block ch.  Meanwhile the other
+    // slab, which held block ch-1, loses that block and receives block ch+1: one barrier per step.
+    // In registers: eprev / ecur / enext = lists of blocks ch-1 / ch / ch+1, eload receives ch+2.
+    for (int ch = chunk_begin; ch < chunk_end; ++ch) {
+        if (ch == wbegin + wchunks) open_window(ch);
+        const int ci = ch - wbegin;
+        __syncthreads();   // block ch is complete in its slab; nobody reads the other slab any more
+        if (ch + 2 < chunk_end)
+            issue_entries(ch + 2, eload);
+        else
+            eload.cntv = 0;
+        if (ci + 1 < wchunks) issue_b_first(ci + 1, bnext);
+        const int par = (ch - chunk_begin) & 1;
+        const float *S = As + par * SLAB;
+        char *other = reinterpret_cast<char *>(As + (par ^ 1) * SLAB);
+        const int cprev = padded_count(eprev), cnext = padded_count(enext);
+        multiply(ci, buse, S, [&]() {
+            apply_round(other, eprev, cprev, false);
+            apply_round(other, enext, cnext, true);
+        });
+        if (cprev > ROUND) apply_rest(other, ch - 1, cprev, false);
+        if (cnext > ROUND) apply_rest(other, ch + 1, cnext, true);
+        eprev = ecur;
+        ecur = enext;
+        enext = eload;
+        buse = bnext;
+    }
+    __syncthreads();   // the slabs are free: the epilogue reuses them
 
     // ---- write C (or this split's partial sums): every element exactly once.
     // Accumulator layout of the 16x16x4 MFMA: lane holds rows 4*s + v (v = 0..3) of column c.
@@ -389,7 +412,7 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     const bool add = p.split_k == 1 && p.accumulate;
     const int64_t wcol0 = ((int64_t)tile_n * NG + wave * GW) * 16;   // first column of this wave
     constexpr int WCOLS = 16 * GW;
-    constexpr bool FITS = NW * RT * 16 * WCOLS <= TM * KCP;
+    constexpr bool FITS = NW * RT * 16 * WCOLS <= 2 * SLAB;
     const bool vec_ok = FITS && (reinterpret_cast<uintptr_t>(out) % 16 == 0) && (ldo % 4 == 0) && wcol0 + WCOLS <= p.N;
     if (vec_ok) {
         float *mine = As + wave * (RT * 16 * WCOLS);
@@ -471,6 +494,8 @@ const VariantEntry g_variants[] = {
     MMM_VARIANT(2, 2, 4),   // 5: 32 x 128   (matrices of at most 32 rows)
     MMM_VARIANT(2, 4, 4),   // 6: 32 x 256
     MMM_VARIANT(2, 1, 4),   // 7: 32 x 64
+    MMM_VARIANT(4, 1, 16),  // 8: 64 x 256, sixteen waves
+    MMM_VARIANT(2, 1, 8),   // 9: 32 x 128, eight waves
 };
 constexpr int32_t kVariants = (int32_t)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -516,9 +541,9 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtyp
     if (pl.workgroups <= 0 || pl.workgroups > 0x7fffffffLL) return hipErrorInvalidValue;
     if (pl.split_k > 1 && (size_t)pl.split_k * (size_t)m->M * (size_t)m->N * sizeof(float) > m->partial_bytes)
         return hipErrorInvalidValue;
-    const int64_t per_chunk = (int64_t)v.info.groups * WPC * sizeof(uint64_t) + sizeof(uint32_t);
+    const int64_t per_chunk = (int64_t)v.info.groups * WPC * sizeof(uint64_t);
     const int64_t gw = v.info.groups / (v.info.threads / 64);
-    int64_t window = 64 / (gw * WPC);   // one map word per lane: 64 words per wave and window
+    int64_t window = list_words(v.info.threads / 64) / (gw * WPC);   // one map word per lane
     if (window > pl.chunks_per_split) window = pl.chunks_per_split;
     if (window < 1) return hipErrorInvalidValue;
     p.window_chunks = (int32_t)window;
