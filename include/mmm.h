@@ -143,9 +143,9 @@ mmm_status mmm_maps_view_derived(const mmm_maps *maps, const uint64_t **a_colany
  *   counts [block]            : number of non-zero elements of A in the block
  *   entries[block][*capacity] : the first counts[block] words describe those
  *       elements, each exactly once, in an order that is fixed for a given A:
- *       low 32 bits  = 16 * (16 * column_in_block + (row_in_block + column_in_block) % 16) + 4 * (row_in_block / 16)
+ *       low 32 bits  = 272 * column_in_block + 16 * (row_in_block % 16) + 4 * (row_in_block / 16)
  *       high 32 bits = the value as IEEE float bits (bf16 widened)
- *     then words {32768, 0} up to the next multiple of 64 (none if the count
+ *     then words {34816, 0} up to the next multiple of 64 (none if the count
  *     is one already); words beyond that are unspecified.
  * Errors: MMM_ERR_INVALID_ARG. */
 mmm_status mmm_maps_view_lists(const mmm_maps *maps, const uint32_t **counts, const uint64_t **entries,

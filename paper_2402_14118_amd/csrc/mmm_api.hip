@@ -11,7 +11,7 @@
 namespace {
 
 constexpr size_t kAlign = 256;
-constexpr int64_t kMaxLd = 1LL << 22;   // largest leading dimension of X and Y the masked GEMM addresses
+constexpr int64_t kMaxLd = (1LL << 22) - 1;   // largest leading dimension of X and Y the masked GEMM addresses
 constexpr size_t kPartialCap = (size_t)64 << 20;   // split-K partial sums: at most 64 MiB
 
 thread_local char g_detail[160] = "";
@@ -85,10 +85,10 @@ mmm_plan make_plan(const mmm_maps *m, int32_t dt)
         // matrices; otherwise the 256-column tile (one workgroup of sixteen waves per CU) when that
         // still gives every CU a workgroup, else the 128-column tile (two workgroups of eight waves)
         if (m->M <= 32) {
-            v = 9;
+            v = 5;
         } else {
             const int64_t t256 = ((m->M + 63) / 64) * ((m->N + 255) / 256);
-            v = t256 >= 256 ? 8 : 3;
+            v = t256 >= 256 ? 1 : 0;
         }
     }
     const mmm_variant_info &vi = mmm_variant((int32_t)v);

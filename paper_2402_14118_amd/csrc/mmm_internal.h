@@ -16,16 +16,17 @@ constexpr int MMM_BT_PIECE = 16;
 constexpr int MMM_AB_ROWS = 64;
 constexpr int MMM_AB_COLS = 128;
 constexpr int MMM_AB_CAP = MMM_AB_ROWS * MMM_AB_COLS;   // list capacity per block: the worst case
-// The LDS slab a block is scattered into is column-major with the rows r, r+16, r+32, r+48 of a
-// column next to each other: one 16-byte read yields the A operands of all four 16-row MFMA tiles
-// for one k, and the 16 lanes of an operand read 256 contiguous bytes.  Inside its column the
-// 16-byte cell of row r sits at slot (r + column) mod 16, so that neighbouring columns of one row
-// (neighbours in a block's list) fall into different LDS banks.  Column MMM_AB_COLS is spare and
-// always zero.
-constexpr int MMM_SLAB_FLOATS = (MMM_AB_COLS + 1) * MMM_AB_ROWS;
+// The LDS slab a block is scattered into is column-major: a column takes MMM_SLAB_COL_BYTES, its
+// first 256 bytes hold the 64 rows with the rows r, r+16, r+32, r+48 next to each other, so one
+// 16-byte read yields the A operands of all four 16-row MFMA tiles for one k and the 16 lanes of an
+// operand read 256 contiguous bytes.  The 16 spare bytes per column shift neighbouring columns by
+// four LDS banks, which spreads the entries of one row of a block (neighbours in its list) over
+// the banks.  Column MMM_AB_COLS is spare and always zero.
+constexpr uint32_t MMM_SLAB_COL_BYTES = 272;
+constexpr int MMM_SLAB_FLOATS = (MMM_AB_COLS + 1) * (int)(MMM_SLAB_COL_BYTES / 4);
 __host__ __device__ constexpr uint32_t mmm_slab_pos(uint32_t row, uint32_t col)   // byte offset of element (row, col)
 {
-    return ((col * 16u + ((row + col) & 15u)) * 4u + (row >> 4)) * 4u;
+    return col * MMM_SLAB_COL_BYTES + (row & 15u) * 16u + (row >> 4) * 4u;
 }
 constexpr uint32_t MMM_SLAB_SPARE = mmm_slab_pos(0, MMM_AB_COLS);
 // Dynamic LDS the masked GEMM may use for map words (static use stays below 44 KiB).

@@ -36,13 +36,17 @@
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 constexpr int TM = MMM_AB_ROWS;   // rows of C per workgroup = rows of a block of A
 constexpr int KC = MMM_AB_COLS;   // k per step = columns of a block of A
 constexpr int WPC = KC / 64;      // map words per step
-constexpr int QB = 6;             // k-list quads per batch
-constexpr int LPAD = 4 * QB;
-
+constexpr int QB = 4;             // k-list quads per batch
+constexpr int BATCH = 4 * QB;      // list slots per batch (a power of two that divides KC)
+constexpr int SLAB = MMM_SLAB_FLOATS;                 // floats per slab
+constexpr uint32_t SLAB_BYTES = (uint32_t)SLAB * 4u;
+constexpr uint32_t COLB = MMM_SLAB_COL_BYTES;         // bytes per slab column; column KC stays zero
+static_assert(WPC == 2, "a step is one pair of map words");
 
 struct MatmulParams {
     const void *Y;
@@ -80,23 +84,30 @@ __device__ __forceinline__ uint32_t xcd_contiguous_id(uint32_t b, uint32_t n)
 // [NG][nwords] 64-bit words (per group: transposed-B word AND column-any word of A)
 extern __shared__ uint64_t mmm_dyn_words[];
 
-// map words one wave expands into k lists per window (fewer for the eight-wave workgroups, whose
+// map words one wave expands into k lists per window (fewer for the larger workgroups, whose
 // lists would otherwise keep a second workgroup off the compute unit)
 constexpr int list_words(int nw) { return nw >= 8 ? 16 : 32; }
 
+// On this machine the fp32 MFMA and the vector ALU do not run side by side on a SIMD: every
+// vector instruction of the inner loop costs matrix time.  The loop is therefore written to
+// need few of them: addresses are a wave-uniform base plus one multiply-add per operand, the
+// k lists are padded so that no index needs clamping, LDS offsets are immediates, and the
+// registers that carry operands from step to step rotate by unrolling, not by moves.
+//
 // RT  16-row MFMA sub-tiles computed (4: all 64 rows of the block; 2: matrices of at most 32 rows)
 // GW  16-column groups per wave, NW waves per workgroup: TN = 16*GW*NW columns
 template <int RT, int GW, int NW, typename T, bool BW8>
-__global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams p)
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8 && GW == 1 ? 4 : 2))) void mmm_matmul_kernel(const MatmulParams p)
 {
     constexpr int NG = NW * GW;
     constexpr int NT = NW * 64;
     constexpr int EPT = 1024 / NT;    // list entries of A per thread and round
     constexpr int ROUND = NT * EPT;   // list entries one round of the workgroup moves
-    constexpr int SLAB = MMM_SLAB_FLOATS;   // floats per slab; column KC stays zero (the A operand of a k-list slot past the end)
     constexpr int LW = list_words(NW);
     constexpr int SEG = LW / GW;      // lanes (= map words) per group: SEG / WPC steps per window
     constexpr int REGION = SEG * 64;  // list bytes per group: the worst case
+    constexpr uint32_t ESZ = (uint32_t)sizeof(T);
+    typedef float avec __attribute__((ext_vector_type(RT)));   // A operands of the RT row tiles for one k
 
     __shared__ __align__(16) float As[2 * SLAB];       // two slabs: one is multiplied from while the other changes
     __shared__ uint8_t lists[NW][GW * REGION + 4];     // per wave: k lists of its groups for one window
@@ -114,9 +125,7 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     const int chunk_begin = split * p.chunks_per_split;
     const int chunk_end = min(chunk_begin + p.chunks_per_split, p.chunks_total);
     const int nwords = p.window_chunks * WPC;
-
-    const T *Y = static_cast<const T *>(p.Y);
-    const uint32_t ldy32 = (uint32_t)p.ldy;
+    const uint32_t ldyb = (uint32_t)p.ldy * ESZ;   // bytes per row of Y (below 2^24: the host checks)
 
     floatx4 acc[GW][RT];
 #pragma unroll
@@ -131,7 +140,7 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     int wchunks = 0;            // steps in the current window
 
     // map words of the steps [wb, wb + window_chunks) -> LDS
-    auto load_words = [&](int wb) {
+    auto load_words = [&](int wb) __attribute__((always_inline)) {
         for (int idx = tid; idx < NG * nwords; idx += NT) {
             const int gi = idx / nwords, wi = idx % nwords;
             const int64_t widx = (int64_t)wb * WPC + wi;
@@ -164,242 +173,279 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     struct Entries {
         uint32_t pos[EPT];   // byte offset inside a slab
         uint32_t val[EPT];   // float bit pattern
-        uint32_t cntv;       // entries of the block (the same value in every lane); 0: no block
+        uint32_t cntv;       // entries of the block (the same value in every lane)
+        int valid;           // wave-uniform: 0 if there is no such block in this workgroup's K range
     };
-    // First batch of B operands of one step, per group of this wave.
-    struct BFirst {
-        float b[GW][QB];
-        int kk[GW][QB];      // the listed k they belong to
-        int cnt[GW], start[GW];
-    };
-    Entries eprev, ecur, enext, eload;
-    BFirst buse, bnext;
-    eprev.cntv = ecur.cntv = enext.cntv = eload.cntv = 0;
+    Entries E0, E1, E2, E3;
+    E0.cntv = E1.cntv = E2.cntv = E3.cntv = 0;
+    E0.valid = E1.valid = E2.valid = E3.valid = 0;
 
     const int wave_e0 = wave * 64;
+    const char *ent_tile = reinterpret_cast<const char *>(p.a_ent) + (size_t)tile_m * p.KBA * (MMM_AB_CAP * 8);
+    const char *cnt_tile = reinterpret_cast<const char *>(p.a_cnt) + (size_t)tile_m * p.KBA * 4;
+    const uint32_t tid8 = (uint32_t)tid * 8u;
+    // the count comes through the vector memory path like the entries, so that it arrives in
+    // order with them (this lane offset is always 0)
+    const uint32_t zoff = (uint32_t)(lane & p.zero) * 4u;
     // request the first round of the list of block ch (and its count) into registers
-    auto issue_entries = [&](int ch, Entries &e) {
-        const size_t blk = (size_t)tile_m * p.KBA + ch;
-        // the count comes through the vector memory path like the entries, so that it arrives in
-        // order with them (the lane term is always 0)
-        e.cntv = p.a_cnt[blk + (size_t)(lane & p.zero)];
-        const uint2 *ent = p.a_ent + blk * MMM_AB_CAP + tid;
-        // Loaded unconditionally (a round always lies inside the block's list area); what lies
-        // past the padded count is never used.  No branch, so nothing here waits for the data.
+    auto issue_entries = [&](int ch, Entries &e) __attribute__((always_inline)) {
+        // Everything is loaded unconditionally, so that nothing here waits for data: past the end
+        // of the K range the last block is read again and marked invalid; a round always lies
+        // inside the block's list area, and what lies past the padded count is never used.
+        e.valid = ch < chunk_end;
+        ch = min(ch, p.chunks_total - 1);
+        const char *eb = ent_tile + (size_t)ch * (MMM_AB_CAP * 8);   // wave-uniform
+        e.cntv = *reinterpret_cast<const uint32_t *>(cnt_tile + (size_t)ch * 4 + zoff);
 #pragma unroll
         for (int j = 0; j < EPT; ++j) {
-            const uint2 v = ent[j * NT];
+            const uint2 v = *reinterpret_cast<const uint2 *>(eb + tid8 + (uint32_t)(j * NT * 8));
             e.pos[j] = v.x;
             e.val[j] = v.y;
         }
     };
-    auto padded_count = [&](const Entries &e) -> int {
-        return ((int)__builtin_amdgcn_readfirstlane(e.cntv) + 63) & ~63;
+    auto padded_count = [&](const Entries &e) __attribute__((always_inline)) -> int {
+        return e.valid ? ((int)__builtin_amdgcn_readfirstlane(e.cntv) + 63) & ~63 : 0;
     };
     // A slab is filled and emptied with integer adds on the float bit patterns: a cell goes
     // 0 -> bits -> 0 exactly, whatever the order in which the adds of different threads land, so
     // removing block c-1 from a slab and putting block c+1 into it need no barrier between them.
-    auto slab_add = [&](char *slab, uint32_t pos, uint32_t v) {
-        __hip_atomic_fetch_add(reinterpret_cast<uint32_t *>(slab + pos), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    auto slab_add = [&](char *slab, uint32_t pos, uint32_t v, bool fill) __attribute__((always_inline)) {
+        uint32_t *cell = reinterpret_cast<uint32_t *>(slab + pos);
+        if (fill)
+            __hip_atomic_fetch_add(cell, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        else
+            __hip_atomic_fetch_sub(cell, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     };
     // the first round of a list, from registers
-    auto apply_round = [&](char *slab, const Entries &e, int cnt, bool fill) {
+    auto apply_round = [&](char *slab, const Entries &e, int cnt, bool fill) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < EPT; ++j)
-            if (wave_e0 + j * NT < cnt) slab_add(slab, e.pos[j], fill ? e.val[j] : 0u - e.val[j]);
+            if (wave_e0 + j * NT < cnt) slab_add(slab, e.pos[j], e.val[j], fill);
     };
     // blocks with more entries than one round: the rest is fetched and applied on the spot
-    auto apply_rest = [&](char *slab, int ch, int cnt, bool fill) {
-        const uint2 *ent = p.a_ent + ((size_t)tile_m * p.KBA + ch) * MMM_AB_CAP;
+    auto apply_rest = [&](char *slab, int ch, int cnt, bool fill) __attribute__((always_inline)) {
+        const uint2 *ent = reinterpret_cast<const uint2 *>(ent_tile + (size_t)ch * (MMM_AB_CAP * 8));
         for (int e = ROUND + tid; e < cnt; e += NT) {
             const uint2 v = ent[e];
-            slab_add(slab, v.x, fill ? v.y : 0u - v.y);
+            slab_add(slab, v.x, v.y, fill);
         }
     };
 
     // ---- k lists.  Once per window every wave turns the map words of its groups into compacted
-    // lists of live k: lane (g, w) owns word w of group g, a segmented prefix sum of the popcounts
-    // gives every word its place in the list of its group, and each lane then writes out the bit
-    // positions of its own word.  Entries are step-relative k (0..127); the entries of one step
-    // are contiguous, and `pref` (read with readlane) tells where each step starts.
-    uint32_t pref = 0, incl = 0;          // exclusive / inclusive popcount prefix of this lane's word inside its group
-    auto build_lists = [&](int nchunks) {
+    // lists of live k: lane (g, w) owns word w of group g; the two words of a step are neighbours.
+    // A prefix sum over the steps' list lengths, each rounded up to whole batches of 4 * QB slots,
+    // gives every step its place in the list of its group, and each lane then writes out the bit
+    // positions of its own word.  Entries are step-relative k (0..127).  The slots that round a
+    // step's list up repeat its last k, so that a batch can always be read without clamping and
+    // always names rows of B that may be read.
+    uint32_t lpos = 0, ltot = 0;   // list position of this lane's word; live k of this lane's step
+    auto build_lists = [&](int nchunks) __attribute__((always_inline)) {
         const int g = (lane / SEG) % GW, wi = lane % SEG;
         uint64_t m = (lane < LW && wi < nchunks * WPC) ? mmm_dyn_words[(wave * GW + g) * nwords + wi] : 0ull;
         const uint32_t cnt = (uint32_t)__popcll(m);
-        incl = cnt;
+        const uint32_t top = cnt ? (uint32_t)(wi & 1) * 64u + 63u - (uint32_t)__clzll((long long)m) : 0u;   // last k of this word
+        const uint32_t ocnt = (uint32_t)__shfl_xor((int)cnt, 1, 64);
+        const uint32_t otop = (uint32_t)__shfl_xor((int)top, 1, 64);
+        const uint32_t live = cnt + ocnt, PT = (live + (uint32_t)BATCH - 1u) & ~((uint32_t)BATCH - 1u);
+        uint32_t incl = (wi & 1) ? 0u : PT;   // the even lane of a step carries its padded length
 #pragma unroll
         for (int d = 1; d < SEG; d <<= 1) {
             const uint32_t o = __shfl_up(incl, d, 64);
             if (wi >= d) incl += o;
         }
-        pref = incl - cnt;
-        uint8_t *dst = &lists[wave][g * REGION + pref];
-        const uint32_t half = (uint32_t)(wi % WPC) * 64u;
+        const uint32_t step_start = incl - PT;   // both lanes of a step see the same inclusive sum
+        lpos = step_start + ((wi & 1) ? ocnt : 0u);
+        ltot = live;
+        uint8_t *lst = &lists[wave][g * REGION];
+        uint8_t *dst = lst + lpos;
+        const uint32_t half = (uint32_t)(wi & 1) * 64u;
         while (m != 0) {   // as many rounds as the fullest word of the wave has bits
             *dst++ = (uint8_t)(half + (uint32_t)__ffsll((unsigned long long)m) - 1u);
             m &= m - 1;
         }
+        if ((wi & 1) && live != 0) {
+            const uint8_t last = (uint8_t)(cnt ? top : otop);
+            for (uint32_t i = live; i < PT; ++i) lst[step_start + i] = last;
+        }
     };
     // first list slot and number of live k of step ci for group g
-    auto step_range = [&](int ci, int g, int &start, int &n) {
-        start = (int)__builtin_amdgcn_readlane(pref, g * SEG + ci * WPC);
-        n = (int)__builtin_amdgcn_readlane(incl, g * SEG + ci * WPC + WPC - 1) - start;
+    auto step_range = [&](int ci, int g, int &start, int &n) __attribute__((always_inline)) {
+        start = (int)__builtin_amdgcn_readlane(lpos, g * SEG + ci * WPC);
+        n = (int)__builtin_amdgcn_readlane(ltot, g * SEG + ci * WPC);
     };
 
-    // B operands.  Every load is unconditional and in bounds: a slot past the end of the list
-    // re-reads the last listed row (its A operand is the zero column of the slab, so the product
-    // vanishes), and lanes past column N re-read column N-1 (their results are never written).
-    const int64_t col_base = ((int64_t)tile_n * NG + wave * GW) * 16 + c;   // column of this lane in its first group
-    int coff[GW];
+    // B operands.  Every load is in bounds: list slots past a step's last quad are not read (the
+    // last quad is read again instead), the slots that pad the last quad repeat the last listed
+    // row (their A operand is the zero column of the slab, so the product vanishes), and lanes
+    // past column N re-read column N-1 (their results are never written).
+    const int64_t wcol0 = ((int64_t)tile_n * NG + wave * GW) * 16;   // first column of this wave
+    const int64_t wcolb = min(wcol0, p.N - 1);                       // the column the wave-uniform base points at
+    uint32_t coffb[GW];   // byte offset of this lane's column of group g from that base
 #pragma unroll
-    for (int g = 0; g < GW; ++g) coff[g] = (int)(min(col_base + g * 16, p.N - 1) - col_base);
-    auto load_b = [&](const T *Yc, int64_t k0, int kb, int g) -> float {
-        float v = to_f32<T>(Yc[(int)__umul24((uint32_t)kb, ldy32) + coff[g]]);
+    for (int g = 0; g < GW; ++g) coffb[g] = (uint32_t)(min(wcol0 + g * 16 + c, p.N - 1) - wcolb) * ESZ;
+    const char *Ywave = static_cast<const char *>(p.Y) + wcolb * ESZ;
+    const uint32_t c16 = (uint32_t)c * 16u;
+    auto load_b = [&](const char *Yst, int64_t k0, uint32_t kb, int g) __attribute__((always_inline)) -> float {
+        float v = to_f32<T>(*reinterpret_cast<const T *>(Yst + (__umul24(kb, ldyb) + coffb[g])));
         if (BW8) {   // a group spans two blocks: take only this lane's own block
-            const int64_t blk = (col_base + coff[g]) >> 3;
+            const int64_t blk = (wcolb + coffb[g] / ESZ) >> 3;
             if (!((p.b_bits[(k0 + kb) * p.WB + (blk >> 6)] >> (blk & 63)) & 1ull)) v = 0.f;
         }
         return v;
     };
-    // list slot t of a step with n live k: the listed k, clamped to the last one
-    auto list_k = [&](const uint8_t *lst, int t, int n) -> int { return lst[min(t, n - 1)]; };
-    auto issue_b_first = [&](int ci, BFirst &f) {
+    // One batch of a step's list: for each of its quads the B operand of this lane's slot and the
+    // slab offset of the matching A operand (the zero column for the slots that pad the list).
+    // lst_s: this lane's first slot of the batch; left: live k from the batch's first slot on.
+    uint32_t slotv[QB];
+#pragma unroll
+    for (int u = 0; u < QB; ++u) slotv[u] = (uint32_t)(4 * u + s);
+    const uint32_t zero_off = (uint32_t)KC * COLB + c16;
+    auto fetch_batch = [&](const char *Yst, int64_t k0, const uint8_t *lst_s, int left, int g, float (&b)[QB],
+                           uint32_t (&aoff)[QB]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < QB; ++u) {
+            const uint32_t kk = lst_s[4 * u];
+            b[u] = load_b(Yst, k0, kk, g);
+            aoff[u] = (int)slotv[u] < left ? __umul24(kk, COLB) + c16 : zero_off;
+        }
+    };
+    // First batch of B operands of one step, per group of this wave.
+    struct BFirst {
+        float b[GW][QB];
+        uint32_t aoff[GW][QB];   // where the matching A operands sit in a slab
+        int n[GW], start[GW];
+    };
+    BFirst BP, BQ;
+    // Yst: row k0 of Y at the wave's base column (wave-uniform)
+    auto issue_b_first = [&](int ci, const char *Yst, BFirst &f) __attribute__((always_inline)) {
         const int64_t k0 = (int64_t)(wbegin + ci) * KC;
-        const T *Yc = Y + k0 * p.ldy + col_base;
 #pragma unroll
         for (int g = 0; g < GW; ++g) {
-            step_range(ci, g, f.start[g], f.cnt[g]);
-            if (f.cnt[g] > 0) {
-                const uint8_t *lst = &lists[wave][g * REGION + f.start[g]];
-#pragma unroll
-                for (int u = 0; u < QB; ++u) {
-                    f.kk[g][u] = list_k(lst, 4 * u + s, f.cnt[g]);
-                    f.b[g][u] = load_b(Yc, k0, f.kk[g][u], g);
-                }
-            }
+            step_range(ci, g, f.start[g], f.n[g]);
+            if (f.n[g] > 0) fetch_batch(Yst, k0, &lists[wave][g * REGION + f.start[g]] + s, f.n[g], g, f.b[g], f.aoff[g]);
         }
     };
 
-    // ---- multiply step ci from slab S: 4 listed k per MFMA.  `between` runs after the first A
-    // operands have been requested and before the first MFMA.
-    auto multiply = [&](int ci, const BFirst &f, const float *S, auto &&between) {
-        const int64_t k0 = (int64_t)(wbegin + ci) * KC;
-        const T *Yc = Y + k0 * p.ldy + col_base;
-        // First batch of every group: the listed k are already in registers, so all A operands
-        // are requested at once, then multiplied.
+    // ---- multiply step ci from the slab at byte address S: 4 listed k per MFMA.  `between`
+    // runs after the first batch.  Yst: row k0 of Y of this step at the wave's base column.
+    auto mfma_quad = [&](int g, const avec &a, float b) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r) acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r], b, acc[g][r], 0, 0, 0);
+    };
+    // the quads of one batch that hold a live k: `left` live k from the batch's first slot on
+    auto mfma_batch = [&](int g, const avec (&a)[QB], const float (&b)[QB], int left) __attribute__((always_inline)) {
+        mfma_quad(g, a[0], b[0]);
+        if (left > 4) {
+            mfma_quad(g, a[1], b[1]);
+            if (left > 8) {
+                mfma_quad(g, a[2], b[2]);
+                if (left > 12) mfma_quad(g, a[3], b[3]);
+            }
+        }
+    };
+    static_assert(QB == 4, "mfma_batch is written out for four quads");
+    auto multiply = [&](int ci, const BFirst &f, const char *S, const char *Yst, auto &&between) __attribute__((always_inline)) {
+        // First batch of every group: the slab offsets are already in registers, so all A operands
+        // are requested at once (those of quads without a live k too: they are in bounds, and a
+        // branch costs more than the read), then multiplied.
         {
-            float a[GW][QB][RT];
+            avec a[GW][QB];
 #pragma unroll
             for (int g = 0; g < GW; ++g) {
+                if (f.n[g] > 0) {
 #pragma unroll
-                for (int u = 0; u < QB; ++u) {
-                    if (4 * u < f.cnt[g]) {
-                        const int kk = 4 * u + s < f.cnt[g] ? f.kk[g][u] : KC;   // KC: the zero column
-#pragma unroll
-                        for (int r = 0; r < RT; ++r) a[g][u][r] = S[kk * 64 + ((c + kk) & 15) * 4 + r];
-                    }
+                    for (int u = 0; u < QB; ++u) a[g][u] = *reinterpret_cast<const avec *>(S + f.aoff[g][u]);
                 }
             }
+#pragma unroll
+            for (int g = 0; g < GW; ++g)
+                if (f.n[g] > 0) mfma_batch(g, a[g], f.b[g], f.n[g]);
             between();
-#pragma unroll
-            for (int g = 0; g < GW; ++g) {
-#pragma unroll
-                for (int u = 0; u < QB; ++u) {
-                    if (4 * u < f.cnt[g]) {
-#pragma unroll
-                        for (int r = 0; r < RT; ++r)
-                            acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[g][u][r], f.b[g][u], acc[g][r], 0, 0, 0);
-                    }
-                }
-            }
         }
         // further batches of long lists: B operands one batch ahead
 #pragma unroll
         for (int g = 0; g < GW; ++g) {
-            const int n = f.cnt[g];
-            if (n <= LPAD) continue;
-            const uint8_t *lst = &lists[wave][g * REGION + f.start[g]];
+            const int n = f.n[g];
+            if (n <= BATCH) continue;
+            const int64_t k0 = (int64_t)(wbegin + ci) * KC;
+            const uint8_t *lst_s = &lists[wave][g * REGION + f.start[g]] + s;
             float b[QB];
-#pragma unroll
-            for (int u = 0; u < QB; ++u) b[u] = load_b(Yc, k0, list_k(lst, LPAD + 4 * u + s, n), g);
-            for (int q = LPAD; q < n; q += LPAD) {
+            uint32_t ao[QB];
+            fetch_batch(Yst, k0, lst_s + BATCH, n - BATCH, g, b, ao);
+            for (int t = BATCH; t < n; t += BATCH) {   // t: first slot of the batch in b / ao
                 float bn[QB];
-                if (q + LPAD < n) {
-#pragma unroll
-                    for (int u = 0; u < QB; ++u) bn[u] = load_b(Yc, k0, list_k(lst, q + LPAD + 4 * u + s, n), g);
+                uint32_t aon[QB];
+                if (t + BATCH < n) {
+                    fetch_batch(Yst, k0, lst_s + t + BATCH, n - t - BATCH, g, bn, aon);
                 } else {
 #pragma unroll
-                    for (int u = 0; u < QB; ++u) bn[u] = 0.f;
-                }
-                float a[QB][RT];
-#pragma unroll
-                for (int u = 0; u < QB; ++u) {
-                    const int t = q + 4 * u + s;
-                    const int kk = t < n ? (int)lst[min(t, n - 1)] : KC;
-#pragma unroll
-                    for (int r = 0; r < RT; ++r) a[u][r] = S[kk * 64 + ((c + kk) & 15) * 4 + r];
-                }
-#pragma unroll
-                for (int u = 0; u < QB; ++u) {
-                    if (q + 4 * u < n) {
-#pragma unroll
-                        for (int r = 0; r < RT; ++r)
-                            acc[g][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][r], b[u], acc[g][r], 0, 0, 0);
+                    for (int u = 0; u < QB; ++u) {
+                        bn[u] = 0.f;
+                        aon[u] = zero_off;
                     }
                 }
+                avec a[QB];
 #pragma unroll
-                for (int u = 0; u < QB; ++u) b[u] = bn[u];
+                for (int u = 0; u < QB; ++u) a[u] = *reinterpret_cast<const avec *>(S + ao[u]);
+                mfma_batch(g, a, b, n - t);
+#pragma unroll
+                for (int u = 0; u < QB; ++u) {
+                    b[u] = bn[u];
+                    ao[u] = aon[u];
+                }
             }
         }
     };
 
+    const int64_t ystride = (int64_t)KC * ldyb;   // bytes of Y per step
     // start of a window: map words -> LDS -> k lists, and the first B operands of its first step
-    auto open_window = [&](int wb) {
+    auto open_window = [&](int wb, BFirst &f) __attribute__((always_inline)) {
         wbegin = wb;
         wchunks = min(p.window_chunks, chunk_end - wb);
         load_words(wb);
         __syncthreads();
         build_lists(wchunks);
-        issue_b_first(0, buse);
+        issue_b_first(0, Ywave + wb * ystride, f);
     };
 
-    if (chunk_begin < chunk_end) {
-        issue_entries(chunk_begin, ecur);
-        if (chunk_begin + 1 < chunk_end) issue_entries(chunk_begin + 1, enext);
-        open_window(chunk_begin);   // its barrier also makes the zeroed slabs visible
-        {
-            const int cnt = padded_count(ecur);
-            apply_round(reinterpret_cast<char *>(As), ecur, cnt, true);
-            if (cnt > ROUND) apply_rest(reinterpret_cast<char *>(As), chunk_begin, cnt, true);
-        }
-    }
     // Step ch multiplies from slab (ch - chunk_begin) & 1, which holds block ch.  Meanwhile the other
     // slab, which held block ch-1, loses that block and receives block ch+1: one barrier per step.
-    // In registers: eprev / ecur / enext = lists of blocks ch-1 / ch / ch+1, eload receives ch+2.
-    for (int ch = chunk_begin; ch < chunk_end; ++ch) {
-        if (ch == wbegin + wchunks) open_window(ch);
+    // prev / cur / next hold the lists of blocks ch-1 / ch / ch+1 (cur only waits for its turn as
+    // prev), load receives that of block ch+2; use / next hold the first B operands of steps ch / ch+1.
+    const char *Ycur = Ywave + chunk_begin * ystride;   // row ch * KC of Y at the wave's base column
+    auto step = [&](int ch, int par, Entries &prev, Entries &next, Entries &load, const BFirst &use, BFirst &nextb) __attribute__((always_inline)) {
         const int ci = ch - wbegin;
         __syncthreads();   // block ch is complete in its slab; nobody reads the other slab any more
-        if (ch + 2 < chunk_end)
-            issue_entries(ch + 2, eload);
-        else
-            eload.cntv = 0;
-        if (ci + 1 < wchunks) issue_b_first(ci + 1, bnext);
-        const int par = (ch - chunk_begin) & 1;
-        const float *S = As + par * SLAB;
-        char *other = reinterpret_cast<char *>(As + (par ^ 1) * SLAB);
-        const int cprev = padded_count(eprev), cnext = padded_count(enext);
-        multiply(ci, buse, S, [&]() {
-            apply_round(other, eprev, cprev, false);
-            apply_round(other, enext, cnext, true);
+        issue_entries(ch + 2, load);
+        if (ci + 1 < wchunks) issue_b_first(ci + 1, Ycur + ystride, nextb);
+        const char *S = reinterpret_cast<const char *>(As) + par * SLAB_BYTES;
+        char *other = reinterpret_cast<char *>(As) + (par ^ 1) * SLAB_BYTES;
+        const int cprev = padded_count(prev), cnext = padded_count(next);
+        multiply(ci, use, S, Ycur, [&]() {
+            apply_round(other, prev, cprev, false);
+            apply_round(other, next, cnext, true);
         });
         if (cprev > ROUND) apply_rest(other, ch - 1, cprev, false);
         if (cnext > ROUND) apply_rest(other, ch + 1, cnext, true);
-        eprev = ecur;
-        ecur = enext;
-        enext = eload;
-        buse = bnext;
+        Ycur += ystride;
+    };
+
+    if (chunk_begin < chunk_end) {
+        issue_entries(chunk_begin, E1);
+        issue_entries(chunk_begin + 1, E2);
+        open_window(chunk_begin, BP);   // its barrier also makes the zeroed slabs visible
+        const int cnt = padded_count(E1);
+        apply_round(reinterpret_cast<char *>(As), E1, cnt, true);
+        if (cnt > ROUND) apply_rest(reinterpret_cast<char *>(As), chunk_begin, cnt, true);
+    }
+    // Four steps per trip, so that the roles of the register sets rotate by name.  A window that is
+    // not the last one holds a multiple of four steps (the host picks 4, 8 or 16).
+    for (int ch = chunk_begin; ch < chunk_end; ch += 4) {
+        if (ch == wbegin + wchunks) open_window(ch, BP);
+        step(ch, 0, E0, E2, E3, BP, BQ);
+        if (ch + 1 < chunk_end) step(ch + 1, 1, E1, E3, E0, BQ, BP);
+        if (ch + 2 < chunk_end) step(ch + 2, 0, E2, E0, E1, BP, BQ);
+        if (ch + 3 < chunk_end) step(ch + 3, 1, E3, E1, E2, BQ, BP);
     }
     __syncthreads();   // the slabs are free: the epilogue reuses them
 
@@ -410,7 +456,6 @@ __global__ __launch_bounds__(NW * 64) void mmm_matmul_kernel(const MatmulParams 
     float *out = p.split_k > 1 ? p.P + (int64_t)split * p.M * p.N : p.C;
     const int64_t ldo = p.split_k > 1 ? p.N : p.ldc;
     const bool add = p.split_k == 1 && p.accumulate;
-    const int64_t wcol0 = ((int64_t)tile_n * NG + wave * GW) * 16;   // first column of this wave
     constexpr int WCOLS = 16 * GW;
     constexpr bool FITS = NW * RT * 16 * WCOLS <= 2 * SLAB;
     const bool vec_ok = FITS && (reinterpret_cast<uintptr_t>(out) % 16 == 0) && (ldo % 4 == 0) && wcol0 + WCOLS <= p.N;
@@ -486,16 +531,14 @@ struct VariantEntry {
     }
 
 const VariantEntry g_variants[] = {
-    MMM_VARIANT(4, 2, 4),   // 0: 64 x 128
-    MMM_VARIANT(4, 4, 4),   // 1: 64 x 256
-    MMM_VARIANT(4, 1, 4),   // 2: 64 x 64
-    MMM_VARIANT(4, 1, 8),   // 3: 64 x 128, eight waves
-    MMM_VARIANT(4, 2, 8),   // 4: 64 x 256, eight waves
-    MMM_VARIANT(2, 2, 4),   // 5: 32 x 128   (matrices of at most 32 rows)
-    MMM_VARIANT(2, 4, 4),   // 6: 32 x 256
-    MMM_VARIANT(2, 1, 4),   // 7: 32 x 64
-    MMM_VARIANT(4, 1, 16),  // 8: 64 x 256, sixteen waves
-    MMM_VARIANT(2, 1, 8),   // 9: 32 x 128, eight waves
+    MMM_VARIANT(4, 1, 8),    // 0: 64 x 128, eight waves
+    MMM_VARIANT(4, 1, 16),   // 1: 64 x 256, sixteen waves
+    MMM_VARIANT(4, 1, 4),    // 2: 64 x 64, four waves
+    MMM_VARIANT(4, 2, 8),    // 3: 64 x 256, eight waves
+    MMM_VARIANT(4, 2, 4),    // 4: 64 x 128, four waves
+    MMM_VARIANT(2, 1, 8),    // 5: 32 x 128, eight waves   (matrices of at most 32 rows)
+    MMM_VARIANT(2, 1, 4),    // 6: 32 x 64
+    MMM_VARIANT(2, 2, 4),    // 7: 32 x 128, four waves
 };
 constexpr int32_t kVariants = (int32_t)(sizeof(g_variants) / sizeof(g_variants[0]));
 

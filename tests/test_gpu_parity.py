@@ -45,12 +45,12 @@ def check_lists(run, ab, w, what):
         for bk in range(KB):
             kp = keep[bm * 64:(bm + 1) * 64, bk * 128:(bk + 1) * 128]
             r, c = np.nonzero(kp)
-            want = (xbits[bm * 64 + r, bk * 128 + c].astype(np.uint64) << np.uint64(32)) | (16 * (16 * c + (r + c) % 16) + 4 * (r // 16)).astype(np.uint64)
+            want = (xbits[bm * 64 + r, bk * 128 + c].astype(np.uint64) << np.uint64(32)) | (272 * c + 16 * (r % 16) + 4 * (r // 16)).astype(np.uint64)
             got = ents[bm * KB + bk]
             n = int(counts[bm, bk])
             assert n == len(want), f"{what}: block ({bm},{bk}) count {n} want {len(want)}"
             np.testing.assert_array_equal(np.sort(got[:n]), np.sort(want), err_msg=f"{what}: block ({bm},{bk}) entries")
-            assert (got[n:] == np.uint64(32768)).all(), f"{what}: block ({bm},{bk}) padding"
+            assert (got[n:] == np.uint64(34816)).all(), f"{what}: block ({bm},{bk}) padding"
 
 
 def check_workload(w, what, exact=False, **ld):
