@@ -86,7 +86,7 @@ extern __shared__ uint64_t mmm_dyn_words[];
 
 // map words one wave expands into k lists per window (fewer for the larger workgroups, whose
 // lists would otherwise keep a second workgroup off the compute unit)
-constexpr int list_words(int nw) { return nw >= 8 ? 16 : 32; }
+constexpr int list_words(int nw) { return nw == 8 ? 16 : 32; }
 
 // On this machine the fp32 MFMA and the vector ALU do not run side by side on a SIMD: every
 // vector instruction of the inner loop costs matrix time.  The loop is therefore written to
