@@ -55,20 +55,17 @@ __device__ __forceinline__ uint32_t order_key(uint32_t u)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__device__ __forceinline__ bool is_nan_bits(uint32_t u) { return (u & 0x7fffffffu) > 0x7f800000u; }
-
 // Element predicate of M, decided on the bit pattern so that no denormal mode
 // of the float pipeline can change a map bit.  Includes the non-zero test.
-__device__ __forceinline__ bool keep_element(uint32_t u, int32_t pred, uint32_t t)
+// `thr` is prepared by the host (see threshold_key): for GT the order key of the
+// threshold, for ABS_GT its magnitude bits; NaN never passes GT / ABS_GT.
+template <int PRED> __device__ __forceinline__ bool keep_element(uint32_t u, uint32_t thr)
 {
-    const bool nz = (u & 0x7fffffffu) != 0;
-    if (pred == MMM_PRED_NONZERO) return nz;
-    if (is_nan_bits(u) || is_nan_bits(t)) return false;
-    if (pred == MMM_PRED_GT) return nz && order_key(u) > order_key(t);
-    // |x| > t
-    const uint32_t at = t & 0x7fffffffu;
-    if ((t & 0x80000000u) && at != 0) return nz;   // negative threshold: every |x| exceeds it
-    return nz && (u & 0x7fffffffu) > at;
+    const uint32_t a = u & 0x7fffffffu;
+    if (PRED == MMM_PRED_NONZERO) return a != 0;
+    const bool ok = a != 0 && a <= 0x7f800000u;
+    if (PRED == MMM_PRED_GT) return ok && order_key(u) > thr;
+    return ok && a > thr;
 }
 
 __device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
@@ -81,7 +78,7 @@ __device__ __forceinline__ uint32_t mbcnt64(uint64_t m)
 // ---- A side: one workgroup = one block of 64 rows x 128 columns ------------------------------
 // Wave w scans rows 8w..8w+7, one 64-column word per load.  Lane 2j+h of the wave ends up
 // holding the bitmap word (row j, half h); entries are appended in (row, column) order.
-template <typename T>
+template <typename T, int PRED>
 __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lane, int wave, uint64_t *red,
                                        uint32_t *tot)
 {
@@ -90,6 +87,10 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
     const int64_t rbase = bi * MMM_AB_ROWS + wave * A_ROWS_PER_WAVE;
     const int64_t w_lo = k_lo / 64;
     const T *X = static_cast<const T *>(p.X);
+    // keep words of the wave's 16 (row, half) pairs, one per lane 2j+h, requested together with X
+    uint64_t kw = ~0ull;
+    if (p.keep_a != nullptr && lane < 2 * A_ROWS_PER_WAVE && rbase + (lane >> 1) < p.M && w_lo + (lane & 1) < p.WA)
+        kw = p.keep_a[(rbase + (lane >> 1)) * p.WA + w_lo + (lane & 1)];
     uint32_t u[A_ROWS_PER_WAVE][A_WORDS];
 #pragma unroll
     for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
@@ -105,9 +106,9 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
     for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
 #pragma unroll
         for (int h = 0; h < A_WORDS; ++h) {
-            const int64_t r = rbase + j;
-            uint64_t m = ballot64(keep_element(u[j][h], p.pred, p.thr_bits));   // lanes past K or M hold +0
-            if (p.keep_a != nullptr && m != 0) m &= p.keep_a[r * p.WA + w_lo + h];   // m != 0: r < M and the word exists
+            uint64_t m = ballot64(keep_element<PRED>(u[j][h], p.thr_bits));   // lanes past K or M hold +0
+            m &= ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(kw >> 32), 2 * j + h) << 32) |
+                 (uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)kw, 2 * j + h);
             colany[h] |= m;
             if (lane == 2 * j + h) mine = m;
         }
@@ -179,38 +180,46 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
     const int64_t nb_left = p.NB - w * 64;
     const uint64_t valid = nb_left >= 64 ? ~0ull : ((1ull << nb_left) - 1ull);
     uint32_t piece_bits = 0;
-#pragma unroll 1
+    // which blocks of the wave's rows the keep bitmaps leave switched on: asked for all rows first,
+    // so that the waits for these small loads overlap
+    uint64_t kept[B_ROWS_PER_WAVE];
+#pragma unroll
+    for (int r = 0; r < B_ROWS_PER_WAVE; ++r) {
+        const int64_t k = kbase + r;
+        kept[r] = 0;
+        if (k < p.K) {
+            kept[r] = valid;
+            if (p.keep_rows != nullptr) kept[r] &= 0ull - ((p.keep_rows[k >> 6] >> (k & 63)) & 1ull);
+            if (p.keep_blocks != nullptr) kept[r] &= p.keep_blocks[k * p.WB + w];
+        }
+    }
+    constexpr int PER = BW <= 16 ? BW : 16;   // loads in flight per lane and row
+#pragma unroll
     for (int r = 0; r < B_ROWS_PER_WAVE; ++r) {
         const int64_t k = kbase + r;
         uint64_t word = 0;
-        if (k < p.K) {
-            uint64_t kept = valid;
-            if (p.keep_rows != nullptr && !((p.keep_rows[k >> 6] >> (k & 63)) & 1ull)) kept = 0;
-            if (p.keep_blocks != nullptr) kept &= p.keep_blocks[k * p.WB + w];
-            if (kept != 0) {
-                const T *row = Y + k * p.ldy + w * 64 * BW;
-                constexpr int BATCH = 8;   // loads in flight per lane
-                uint64_t mine = 0;
-#pragma unroll 1
-                for (int j0 = 0; j0 < BW; j0 += BATCH) {
-                    uint32_t u[BATCH];
+        if (kept[r] != 0) {
+            const T *row = Y + k * p.ldy + w * 64 * BW;
+            uint64_t mine = 0;
 #pragma unroll
-                    for (int j = 0; j < BATCH; ++j) {
-                        const int blk = (j0 + j) * BPL + lane / BW;   // block (inside this word) of this lane's element
-                        u[j] = 0;
-                        if ((kept >> blk) & 1ull) u[j] = f32_bits<T>(row[(j0 + j) * 64 + lane]);
-                    }
+            for (int j0 = 0; j0 < BW; j0 += PER) {
+                uint32_t u[PER];
 #pragma unroll
-                    for (int j = 0; j < BATCH; ++j) {
-                        const uint64_t m = ballot64((u[j] & 0x7fffffffu) != 0);
-                        if (lane / BPL == j0 + j) mine = m;   // lane L collects the load that holds block L
-                    }
+                for (int j = 0; j < PER; ++j) {
+                    const int blk = (j0 + j) * BPL + lane / BW;   // block (inside this word) of this lane's element
+                    u[j] = 0;
+                    if ((kept[r] >> blk) & 1ull) u[j] = f32_bits<T>(row[(j0 + j) * 64 + lane]);
                 }
-                const uint64_t bwmask = BW == 32 ? 0xffffffffull : ((1ull << BW) - 1ull);
-                word = ballot64(((mine >> ((lane % BPL) * BW)) & bwmask) != 0);
+#pragma unroll
+                for (int j = 0; j < PER; ++j) {
+                    const uint64_t m = ballot64((u[j] & 0x7fffffffu) != 0);
+                    if (lane / BPL == j0 + j) mine = m;   // lane L collects the load that holds block L
+                }
             }
-            if (lane == 0) p.b_bits[k * p.WB + w] = word;
+            const uint64_t bwmask = BW == 32 ? 0xffffffffull : ((1ull << BW) - 1ull);
+            word = ballot64(((mine >> ((lane % BPL) * BW)) & bwmask) != 0);
         }
+        if (k < p.K && lane == 0) p.b_bits[k * p.WB + w] = word;
         piece_bits |= (uint32_t)((word >> lane) & 1ull) << (wave * B_ROWS_PER_WAVE + r);
     }
     pieces[wave * 64 + lane] = piece_bits;
@@ -233,7 +242,12 @@ __global__ __launch_bounds__(BUILD_THREADS) void mmm_build_kernel(const BuildPar
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t b = blockIdx.x;
     if (b < p.n_a) {
-        scan_a<T>(p, b, lane, wave, red, tot);
+        if (p.pred == MMM_PRED_NONZERO)
+            scan_a<T, MMM_PRED_NONZERO>(p, b, lane, wave, red, tot);
+        else if (p.pred == MMM_PRED_GT)
+            scan_a<T, MMM_PRED_GT>(p, b, lane, wave, red, tot);
+        else
+            scan_a<T, MMM_PRED_ABS_GT>(p, b, lane, wave, red, tot);
     } else {
         const int64_t bw = p.N / p.NB;
         if (bw == 8)
@@ -282,6 +296,24 @@ __global__ __launch_bounds__(256) void mmm_stats_kernel(const uint64_t *a_bits, 
 
 }   // namespace
 
+// What keep_element compares against.  GT: x > t  <=>  key(x) > key(t) on the order-preserving key
+// (both zeros map to the same key).  ABS_GT: |x| > t; a negative t passes every non-zero x (magnitude
+// bits of x > 0), t = -0 is t = 0.  A NaN threshold passes nothing (nothing exceeds 0xffffffff).
+static uint32_t threshold_key(int32_t pred, float threshold)
+{
+    union { float f; uint32_t u; } cv;
+    cv.f = threshold;
+    uint32_t t = cv.u;
+    const uint32_t at = t & 0x7fffffffu;
+    if (at > 0x7f800000u) return 0xffffffffu;
+    if (pred == MMM_PRED_GT) {
+        if (at == 0) t = 0;
+        return (t & 0x80000000u) ? ~t : (t | 0x80000000u);
+    }
+    if (pred == MMM_PRED_ABS_GT) return (t & 0x80000000u) ? 0u : at;
+    return 0;
+}
+
 hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStream_t s)
 {
     BuildParams p{};
@@ -307,9 +339,7 @@ hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStrea
     p.MT = m->MT;
     p.KBA = m->KBA;
     p.pred = a.pred;
-    union { float f; uint32_t u; } cv;
-    cv.f = a.threshold;
-    p.thr_bits = cv.u;
+    p.thr_bits = threshold_key(a.pred, a.threshold);
     const int64_t n_a = a.X ? m->MBA * m->KBA : 0;
     const int64_t n_b = a.Y ? (m->WA * (64 / MMM_BT_PIECE)) * m->WB : 0;
     if (n_a + n_b <= 0 || n_a + n_b > 0x7fffffffLL) return hipErrorInvalidValue;
