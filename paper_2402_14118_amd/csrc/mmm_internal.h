@@ -29,9 +29,6 @@ __host__ __device__ constexpr uint32_t mmm_slab_pos(uint32_t row, uint32_t col) 
     return col * MMM_SLAB_COL_BYTES + (row & 15u) * 16u + (row >> 4) * 4u;
 }
 constexpr uint32_t MMM_SLAB_SPARE = mmm_slab_pos(0, MMM_AB_COLS);
-// Dynamic LDS the masked GEMM may use for map words (static use stays below 44 KiB).
-constexpr int MMM_MAX_DYN_LDS = 20 * 1024;
-
 struct mmm_maps {
     int64_t M, K, N;
     int32_t bw;

@@ -81,9 +81,6 @@ __device__ __forceinline__ uint32_t xcd_contiguous_id(uint32_t b, uint32_t n)
     return x * q + (x < rem ? x : rem) + i;
 }
 
-// [NG][nwords] 64-bit words (per group: transposed-B word AND column-any word of A)
-extern __shared__ uint64_t mmm_dyn_words[];
-
 // map words one wave expands into k lists per window (fewer for the larger workgroups, whose
 // lists would otherwise keep a second workgroup off the compute unit)
 constexpr int list_words(int nw) { return nw == 8 ? 16 : 32; }
@@ -124,7 +121,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     const int64_t row0 = (int64_t)tile_m * TM;
     const int chunk_begin = split * p.chunks_per_split;
     const int chunk_end = min(chunk_begin + p.chunks_per_split, p.chunks_total);
-    const int nwords = p.window_chunks * WPC;
     const uint32_t ldyb = (uint32_t)p.ldy * ESZ;   // bytes per row of Y (below 2^24: the host checks)
 
     floatx4 acc[GW][RT];
@@ -139,32 +135,28 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     int wbegin = chunk_begin;   // first step of the current window
     int wchunks = 0;            // steps in the current window
 
-    // map words of the steps [wb, wb + window_chunks) -> LDS
-    auto load_words = [&](int wb) __attribute__((always_inline)) {
-        for (int idx = tid; idx < NG * nwords; idx += NT) {
-            const int gi = idx / nwords, wi = idx % nwords;
-            const int64_t widx = (int64_t)wb * WPC + wi;
-            const int64_t G = (int64_t)tile_n * NG + gi;   // global 16-column group
-            uint64_t m = 0;
-            if (widx < p.WA && G * 16 < p.N) {
-                if (p.bw == 16) {
-                    m = p.bt_bits[G * p.WA + widx];
-                } else if (p.bw == 32) {
-                    m = p.bt_bits[(G >> 1) * p.WA + widx];
-                } else {
-                    m = p.bt_bits[(2 * G) * p.WA + widx];
-                    if (2 * G + 1 < p.NB) m |= p.bt_bits[(2 * G + 1) * p.WA + widx];
-                }
-                uint64_t any = 0;   // k whose column of A is zero in all rows of this tile are dropped
-#pragma unroll
-                for (int t = 0; t < RT * 16 / MMM_COLANY_ROWS; ++t) {
-                    const int64_t tt = row0 / MMM_COLANY_ROWS + t;
-                    if (tt < p.MT) any |= p.a_colany[tt * p.WA + widx];
-                }
-                m &= any;
+    // Map word of one 16-column group for 64 values of k: the transposed B map of the group's
+    // block(s), without the k whose column of A is zero in all rows of this tile.
+    auto map_word = [&](int64_t G, int64_t widx) __attribute__((always_inline)) -> uint64_t {
+        uint64_t m = 0;
+        if (widx < p.WA && G * 16 < p.N) {
+            if (p.bw == 16) {
+                m = p.bt_bits[G * p.WA + widx];
+            } else if (p.bw == 32) {
+                m = p.bt_bits[(G >> 1) * p.WA + widx];
+            } else {
+                m = p.bt_bits[(2 * G) * p.WA + widx];
+                if (2 * G + 1 < p.NB) m |= p.bt_bits[(2 * G + 1) * p.WA + widx];
             }
-            mmm_dyn_words[idx] = m;
+            uint64_t any = 0;
+#pragma unroll
+            for (int t = 0; t < RT * 16 / MMM_COLANY_ROWS; ++t) {
+                const int64_t tt = row0 / MMM_COLANY_ROWS + t;
+                if (tt < p.MT) any |= p.a_colany[tt * p.WA + widx];
+            }
+            m &= any;
         }
+        return m;
     };
 
     // One round of a block's non-zero list, in registers: entry tid + j * NT is entry j of this
@@ -239,9 +231,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     // step's list up repeat its last k, so that a batch can always be read without clamping and
     // always names rows of B that may be read.
     uint32_t lpos = 0, ltot = 0;   // list position of this lane's word; live k of this lane's step
-    auto build_lists = [&](int nchunks) __attribute__((always_inline)) {
+    auto build_lists = [&](int wb, int nchunks) __attribute__((always_inline)) {
         const int g = (lane / SEG) % GW, wi = lane % SEG;
-        uint64_t m = (lane < LW && wi < nchunks * WPC) ? mmm_dyn_words[(wave * GW + g) * nwords + wi] : 0ull;
+        uint64_t m = 0;   // every lane fetches its own word: no staging, nothing to wait for but the load
+        if (lane < LW && wi < nchunks * WPC) m = map_word((int64_t)tile_n * NG + wave * GW + g, (int64_t)wb * WPC + wi);
         const uint32_t cnt = (uint32_t)__popcll(m);
         const uint32_t top = cnt ? (uint32_t)(wi & 1) * 64u + 63u - (uint32_t)__clzll((long long)m) : 0u;   // last k of this word
         const uint32_t ocnt = (uint32_t)__shfl_xor((int)cnt, 1, 64);
@@ -402,9 +395,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     auto open_window = [&](int wb, BFirst &f) __attribute__((always_inline)) {
         wbegin = wb;
         wchunks = min(p.window_chunks, chunk_end - wb);
-        load_words(wb);
-        __syncthreads();
-        build_lists(wchunks);
+        build_lists(wb, wchunks);
         issue_b_first(0, Ywave + wb * ystride, f);
     };
 
@@ -433,7 +424,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     if (chunk_begin < chunk_end) {
         issue_entries(chunk_begin, E1);
         issue_entries(chunk_begin + 1, E2);
-        open_window(chunk_begin, BP);   // its barrier also makes the zeroed slabs visible
+        open_window(chunk_begin, BP);
+        __syncthreads();   // the slabs are all zero
         const int cnt = padded_count(E1);
         apply_round(reinterpret_cast<char *>(As), E1, cnt, true);
         if (cnt > ROUND) apply_rest(reinterpret_cast<char *>(As), chunk_begin, cnt, true);
@@ -584,16 +576,14 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtyp
     if (pl.workgroups <= 0 || pl.workgroups > 0x7fffffffLL) return hipErrorInvalidValue;
     if (pl.split_k > 1 && (size_t)pl.split_k * (size_t)m->M * (size_t)m->N * sizeof(float) > m->partial_bytes)
         return hipErrorInvalidValue;
-    const int64_t per_chunk = (int64_t)v.info.groups * WPC * sizeof(uint64_t);
     const int64_t gw = v.info.groups / (v.info.threads / 64);
     int64_t window = list_words(v.info.threads / 64) / (gw * WPC);   // one map word per lane
     if (window > pl.chunks_per_split) window = pl.chunks_per_split;
     if (window < 1) return hipErrorInvalidValue;
     p.window_chunks = (int32_t)window;
-    const size_t dyn = (size_t)(window * per_chunk + 7) / 8 * 8;
     matmul_kernel_fn fn = m->bw == 8 ? (dtype == MMM_BF16 ? v.bf16_bw8 : v.f32_bw8) : (dtype == MMM_BF16 ? v.bf16 : v.f32);
     (void)hipGetLastError();   // drop any stale error another library left on this thread
-    hipLaunchKernelGGL(fn, dim3((uint32_t)pl.workgroups), dim3((uint32_t)v.info.threads), dyn, s, p);
+    hipLaunchKernelGGL(fn, dim3((uint32_t)pl.workgroups), dim3((uint32_t)v.info.threads), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (pl.split_k > 1) {
