@@ -112,6 +112,18 @@ def test_every_variant_and_split(variant, split):
     assert v == variant and s == split
 
 
+@pytest.mark.parametrize("variant", range(mm.mmm_matmul_variant_count()))
+@pytest.mark.parametrize("bw,p_a,p_b", [(16, 0.9, 0.95), (8, 0.15, 0.5), (32, 0.5, 0.1)])
+def test_long_k_dense_lists(variant, bw, p_a, p_b):
+    """K long enough for several list windows in every variant; dense A (blocks with more entries than one round of the
+    workgroup) and dense B (k lists of many batches)."""
+    mm.mmm_set_option("matmul_variant", variant)
+    mm.mmm_set_option("split_k", 1)
+    short = mm.mmm_matmul_variant_name(variant).startswith("R2")
+    w = synth.random_masked(30 if short else 70, 2500, 96, bw, p_a, p_b, 4242 + variant, dist="smallint")
+    check_workload(w, f"long K variant {variant} bw {bw}", exact=True)
+
+
 def test_padded_leading_dimensions_and_unaligned_rows():
     w = synth.random_masked(70, 203, 80, 16, 0.3, 0.5, 31, dist="smallint")
     check_workload(w, "ld padded", exact=True, ldx=209, ldy=83, ldc=91)
