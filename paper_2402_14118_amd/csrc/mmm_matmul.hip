@@ -421,10 +421,34 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
         Ycur += ystride;
     };
 
+    // The same step for the waves that multiply first: what later steps need is requested after the
+    // MFMAs, one step further ahead (step ch+2 goes into the register set step ch has just used up).
+    auto step_mf = [&](int ch, int par, Entries &prev, Entries &next, Entries &load, BFirst &own) __attribute__((always_inline)) {
+        const int ci = ch - wbegin;
+        __syncthreads();
+        const char *S = reinterpret_cast<const char *>(As) + par * SLAB_BYTES;
+        char *other = reinterpret_cast<char *>(As) + (par ^ 1) * SLAB_BYTES;
+        multiply(ci, own, S, Ycur, [&]() {});
+        issue_entries(ch + 2, load);
+        if (ci + 2 < wchunks) issue_b_first(ci + 2, Ycur + 2 * ystride, own);
+        const int cprev = padded_count(prev), cnext = padded_count(next);
+        apply_round(other, prev, cprev, false);
+        apply_round(other, next, cnext, true);
+        if (cprev > ROUND) apply_rest(other, ch - 1, cprev, false);
+        if (cnext > ROUND) apply_rest(other, ch + 1, cnext, true);
+        Ycur += ystride;
+    };
+    // The barrier keeps all waves of the workgroup in the same step.  A step has two halves that do
+    // not depend on each other, requesting (vector and scalar work, LDS look-ups) and multiplying
+    // (matrix pipe), and the two do not overlap inside a SIMD unless different waves are in different
+    // halves: so half of the waves of every SIMD run them in the opposite order.
+    const bool multiply_first = NW >= 8 && ((wave >> 2) & 1) != 0;
+
     if (chunk_begin < chunk_end) {
         issue_entries(chunk_begin, E1);
         issue_entries(chunk_begin + 1, E2);
         open_window(chunk_begin, BP);
+        if (multiply_first && wchunks > 1) issue_b_first(1, Ycur + ystride, BQ);
         __syncthreads();   // the slabs are all zero
         const int cnt = padded_count(E1);
         apply_round(reinterpret_cast<char *>(As), E1, cnt, true);
@@ -432,12 +456,25 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     }
     // Four steps per trip, so that the roles of the register sets rotate by name.  A window that is
     // not the last one holds a multiple of four steps (the host picks 4, 8 or 16).
-    for (int ch = chunk_begin; ch < chunk_end; ch += 4) {
-        if (ch == wbegin + wchunks) open_window(ch, BP);
-        step(ch, 0, E0, E2, E3, BP, BQ);
-        if (ch + 1 < chunk_end) step(ch + 1, 1, E1, E3, E0, BQ, BP);
-        if (ch + 2 < chunk_end) step(ch + 2, 0, E2, E0, E1, BP, BQ);
-        if (ch + 3 < chunk_end) step(ch + 3, 1, E3, E1, E2, BQ, BP);
+    if (!multiply_first) {
+        for (int ch = chunk_begin; ch < chunk_end; ch += 4) {
+            if (ch == wbegin + wchunks) open_window(ch, BP);
+            step(ch, 0, E0, E2, E3, BP, BQ);
+            if (ch + 1 < chunk_end) step(ch + 1, 1, E1, E3, E0, BQ, BP);
+            if (ch + 2 < chunk_end) step(ch + 2, 0, E2, E0, E1, BP, BQ);
+            if (ch + 3 < chunk_end) step(ch + 3, 1, E3, E1, E2, BQ, BP);
+        }
+    } else {
+        for (int ch = chunk_begin; ch < chunk_end; ch += 4) {
+            if (ch == wbegin + wchunks) {
+                open_window(ch, BP);
+                if (wchunks > 1) issue_b_first(1, Ycur + ystride, BQ);
+            }
+            step_mf(ch, 0, E0, E2, E3, BP);
+            if (ch + 1 < chunk_end) step_mf(ch + 1, 1, E1, E3, E0, BQ);
+            if (ch + 2 < chunk_end) step_mf(ch + 2, 0, E2, E0, E1, BP);
+            if (ch + 3 < chunk_end) step_mf(ch + 3, 1, E3, E1, E2, BQ);
+        }
     }
     __syncthreads();   // the slabs are free: the epilogue reuses them
 
