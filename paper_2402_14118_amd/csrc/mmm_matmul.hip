@@ -166,11 +166,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
         uint32_t pos[EPT];   // byte offset inside a slab
         uint32_t val[EPT];   // float bit pattern
         uint32_t cntv;       // entries of the block (the same value in every lane)
-        int valid;           // wave-uniform: 0 if there is no such block in this workgroup's K range
     };
     Entries E0, E1, E2, E3;
     E0.cntv = E1.cntv = E2.cntv = E3.cntv = 0;
-    E0.valid = E1.valid = E2.valid = E3.valid = 0;
 
     const int wave_e0 = wave * 64;
     const char *ent_tile = reinterpret_cast<const char *>(p.a_ent) + (size_t)tile_m * p.KBA * (MMM_AB_CAP * 8);
@@ -182,9 +180,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     // request the first round of the list of block ch (and its count) into registers
     auto issue_entries = [&](int ch, Entries &e) __attribute__((always_inline)) {
         // Everything is loaded unconditionally, so that nothing here waits for data: past the end
-        // of the K range the last block is read again and marked invalid; a round always lies
+        // of the K range the last block is read again (and not used); a round always lies
         // inside the block's list area, and what lies past the padded count is never used.
-        e.valid = ch < chunk_end;
         ch = min(ch, p.chunks_total - 1);
         const char *eb = ent_tile + (size_t)ch * (MMM_AB_CAP * 8);   // wave-uniform
         e.cntv = *reinterpret_cast<const uint32_t *>(cnt_tile + (size_t)ch * 4 + zoff);
@@ -195,8 +192,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
             e.val[j] = v.y;
         }
     };
-    auto padded_count = [&](const Entries &e) __attribute__((always_inline)) -> int {
-        return e.valid ? ((int)__builtin_amdgcn_readfirstlane(e.cntv) + 63) & ~63 : 0;
+    // entries of block ch, rounded up to whole wavefronts; 0 if the block lies outside this workgroup's K range
+    auto padded_count = [&](const Entries &e, int ch) __attribute__((always_inline)) -> int {
+        return ch >= chunk_begin && ch < chunk_end ? ((int)__builtin_amdgcn_readfirstlane(e.cntv) + 63) & ~63 : 0;
     };
     // A slab is filled and emptied with integer adds on the float bit patterns: a cell goes
     // 0 -> bits -> 0 exactly, whatever the order in which the adds of different threads land, so
@@ -411,7 +409,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
         if (ci + 1 < wchunks) issue_b_first(ci + 1, Ycur + ystride, nextb);
         const char *S = reinterpret_cast<const char *>(As) + par * SLAB_BYTES;
         char *other = reinterpret_cast<char *>(As) + (par ^ 1) * SLAB_BYTES;
-        const int cprev = padded_count(prev), cnext = padded_count(next);
+        const int cprev = padded_count(prev, ch - 1), cnext = padded_count(next, ch + 1);
         multiply(ci, use, S, Ycur, [&]() {
             apply_round(other, prev, cprev, false);
             apply_round(other, next, cnext, true);
@@ -421,60 +419,23 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
         Ycur += ystride;
     };
 
-    // The same step for the waves that multiply first: what later steps need is requested after the
-    // MFMAs, one step further ahead (step ch+2 goes into the register set step ch has just used up).
-    auto step_mf = [&](int ch, int par, Entries &prev, Entries &next, Entries &load, BFirst &own) __attribute__((always_inline)) {
-        const int ci = ch - wbegin;
-        __syncthreads();
-        const char *S = reinterpret_cast<const char *>(As) + par * SLAB_BYTES;
-        char *other = reinterpret_cast<char *>(As) + (par ^ 1) * SLAB_BYTES;
-        multiply(ci, own, S, Ycur, [&]() {});
-        issue_entries(ch + 2, load);
-        if (ci + 2 < wchunks) issue_b_first(ci + 2, Ycur + 2 * ystride, own);
-        const int cprev = padded_count(prev), cnext = padded_count(next);
-        apply_round(other, prev, cprev, false);
-        apply_round(other, next, cnext, true);
-        if (cprev > ROUND) apply_rest(other, ch - 1, cprev, false);
-        if (cnext > ROUND) apply_rest(other, ch + 1, cnext, true);
-        Ycur += ystride;
-    };
-    // The barrier keeps all waves of the workgroup in the same step.  A step has two halves that do
-    // not depend on each other, requesting (vector and scalar work, LDS look-ups) and multiplying
-    // (matrix pipe), and the two do not overlap inside a SIMD unless different waves are in different
-    // halves: so half of the waves of every SIMD run them in the opposite order.
-    const bool multiply_first = NW >= 8 && ((wave >> 2) & 1) != 0;
-
     if (chunk_begin < chunk_end) {
         issue_entries(chunk_begin, E1);
         issue_entries(chunk_begin + 1, E2);
         open_window(chunk_begin, BP);
-        if (multiply_first && wchunks > 1) issue_b_first(1, Ycur + ystride, BQ);
         __syncthreads();   // the slabs are all zero
-        const int cnt = padded_count(E1);
+        const int cnt = padded_count(E1, chunk_begin);
         apply_round(reinterpret_cast<char *>(As), E1, cnt, true);
         if (cnt > ROUND) apply_rest(reinterpret_cast<char *>(As), chunk_begin, cnt, true);
     }
     // Four steps per trip, so that the roles of the register sets rotate by name.  A window that is
     // not the last one holds a multiple of four steps (the host picks 4, 8 or 16).
-    if (!multiply_first) {
-        for (int ch = chunk_begin; ch < chunk_end; ch += 4) {
-            if (ch == wbegin + wchunks) open_window(ch, BP);
-            step(ch, 0, E0, E2, E3, BP, BQ);
-            if (ch + 1 < chunk_end) step(ch + 1, 1, E1, E3, E0, BQ, BP);
-            if (ch + 2 < chunk_end) step(ch + 2, 0, E2, E0, E1, BP, BQ);
-            if (ch + 3 < chunk_end) step(ch + 3, 1, E3, E1, E2, BQ, BP);
-        }
-    } else {
-        for (int ch = chunk_begin; ch < chunk_end; ch += 4) {
-            if (ch == wbegin + wchunks) {
-                open_window(ch, BP);
-                if (wchunks > 1) issue_b_first(1, Ycur + ystride, BQ);
-            }
-            step_mf(ch, 0, E0, E2, E3, BP);
-            if (ch + 1 < chunk_end) step_mf(ch + 1, 1, E1, E3, E0, BQ);
-            if (ch + 2 < chunk_end) step_mf(ch + 2, 0, E2, E0, E1, BP);
-            if (ch + 3 < chunk_end) step_mf(ch + 3, 1, E3, E1, E2, BQ);
-        }
+    for (int ch = chunk_begin; ch < chunk_end; ch += 4) {
+        if (ch == wbegin + wchunks) open_window(ch, BP);
+        step(ch, 0, E0, E2, E3, BP, BQ);
+        if (ch + 1 < chunk_end) step(ch + 1, 1, E1, E3, E0, BQ, BP);
+        if (ch + 2 < chunk_end) step(ch + 2, 0, E2, E0, E1, BP, BQ);
+        if (ch + 3 < chunk_end) step(ch + 3, 1, E3, E1, E2, BQ, BP);
     }
     __syncthreads();   // the slabs are free: the epilogue reuses them
 
