@@ -17,7 +17,8 @@
  *     the caller.  The library never allocates or frees device memory and keeps
  *     no pointer to X, Y or C after a call returns.
  *   - Row-major; leading dimensions (ldx, ldy, ldc) are in elements and must be
- *     >= the row length.  C is always float.
+ *     >= the row length; ldx and ldy must be below 2^22 (MMM_ERR_SHAPE
+ *     otherwise).  C is always float.
  *   - Bitmaps: LSB-first little-endian 64-bit words, row-major, every row padded
  *     to whole words, pad bits zero: bit (c mod 64) of word (c div 64) of row r
  *     describes column c of row r.  (The paper prints patterns first-vector-
