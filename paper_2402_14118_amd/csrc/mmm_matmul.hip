@@ -135,24 +135,27 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     int wbegin = chunk_begin;   // first step of the current window
     int wchunks = 0;            // steps in the current window
 
-    // Map word of one 16-column group for 64 values of k: the transposed B map of the group's
-    // block(s), without the k whose column of A is zero in all rows of this tile.
-    auto map_word = [&](int64_t G, int64_t widx) __attribute__((always_inline)) -> uint64_t {
-        uint64_t m = 0;
+    // Half a map word (32 values of k) of one 16-column group: the transposed B map of the group's
+    // block(s), without the k whose column of A is zero in all rows of this tile.  h: which half of
+    // 64-bit word widx (the maps are little-endian, so half h is 32-bit word 2 * widx + h).
+    auto map_half = [&](int64_t G, int64_t widx, int h) __attribute__((always_inline)) -> uint32_t {
+        const uint32_t *bt = reinterpret_cast<const uint32_t *>(p.bt_bits);
+        const uint32_t *ca = reinterpret_cast<const uint32_t *>(p.a_colany);
+        uint32_t m = 0;
         if (widx < p.WA && G * 16 < p.N) {
             if (p.bw == 16) {
-                m = p.bt_bits[G * p.WA + widx];
+                m = bt[(G * p.WA + widx) * 2 + h];
             } else if (p.bw == 32) {
-                m = p.bt_bits[(G >> 1) * p.WA + widx];
+                m = bt[((G >> 1) * p.WA + widx) * 2 + h];
             } else {
-                m = p.bt_bits[(2 * G) * p.WA + widx];
-                if (2 * G + 1 < p.NB) m |= p.bt_bits[(2 * G + 1) * p.WA + widx];
+                m = bt[((2 * G) * p.WA + widx) * 2 + h];
+                if (2 * G + 1 < p.NB) m |= bt[((2 * G + 1) * p.WA + widx) * 2 + h];
             }
-            uint64_t any = 0;
+            uint32_t any = 0;
 #pragma unroll
             for (int t = 0; t < RT * 16 / MMM_COLANY_ROWS; ++t) {
                 const int64_t tt = row0 / MMM_COLANY_ROWS + t;
-                if (tt < p.MT) any |= p.a_colany[tt * p.WA + widx];
+                if (tt < p.MT) any |= ca[(tt * p.WA + widx) * 2 + h];
             }
             m &= any;
         }
@@ -222,47 +225,54 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     };
 
     // ---- k lists.  Once per window every wave turns the map words of its groups into compacted
-    // lists of live k: lane (g, w) owns word w of group g; the two words of a step are neighbours.
-    // A prefix sum over the steps' list lengths, each rounded up to whole batches of 4 * QB slots,
-    // gives every step its place in the list of its group, and each lane then writes out the bit
-    // positions of its own word.  Entries are step-relative k (0..127).  The slots that round a
-    // step's list up repeat its last k, so that a batch can always be read without clamping and
-    // always names rows of B that may be read.
-    uint32_t lpos = 0, ltot = 0;   // list position of this lane's word; live k of this lane's step
+    // lists of live k.  A lane owns 32 values of k of one group (half a map word), so the four lanes
+    // 4j .. 4j+3 of a group's segment own step j.  A prefix sum over the steps' list lengths, each
+    // rounded up to whole batches of 4 * QB slots, gives every step its place in the list of its
+    // group, and each lane then writes out the bit positions of its own half word.  Entries are
+    // step-relative k (0..127).  The slots that round a step's list up repeat its last k, so that
+    // a batch can always be read without clamping and always names rows of B that may be read.
+    constexpr int HSEG = 2 * SEG;   // lanes per group
+    uint32_t lpos = 0, ltot = 0;    // list position of this lane's half word; live k of this lane's step
     auto build_lists = [&](int wb, int nchunks) __attribute__((always_inline)) {
-        const int g = (lane / SEG) % GW, wi = lane % SEG;
-        uint64_t m = 0;   // every lane fetches its own word: no staging, nothing to wait for but the load
-        if (lane < LW && wi < nchunks * WPC) m = map_word((int64_t)tile_n * NG + wave * GW + g, (int64_t)wb * WPC + wi);
-        const uint32_t cnt = (uint32_t)__popcll(m);
-        const uint32_t top = cnt ? (uint32_t)(wi & 1) * 64u + 63u - (uint32_t)__clzll((long long)m) : 0u;   // last k of this word
-        const uint32_t ocnt = (uint32_t)__shfl_xor((int)cnt, 1, 64);
-        const uint32_t otop = (uint32_t)__shfl_xor((int)top, 1, 64);
-        const uint32_t live = cnt + ocnt, PT = (live + (uint32_t)BATCH - 1u) & ~((uint32_t)BATCH - 1u);
-        uint32_t incl = (wi & 1) ? 0u : PT;   // the even lane of a step carries its padded length
+        const int g = (lane / HSEG) % GW, hi = lane % HSEG;   // hi: half word inside the group's window
+        const int q = hi & 3;                                  // place inside the step
+        uint32_t m = 0;   // every lane fetches its own half word: no staging, nothing to wait for but the load
+        if (lane < 2 * LW && hi < nchunks * 4)
+            m = map_half((int64_t)tile_n * NG + wave * GW + g, (int64_t)wb * WPC + (hi >> 1), hi & 1);
+        const uint32_t cnt = (uint32_t)__popc(m);
+        const int top = cnt ? q * 32 + 31 - __clz((int)m) : -1;   // last k of this half word
+        // the four lanes of a step: counts of the lanes before this one, the step's total and last k
+        const uint32_t c1 = (uint32_t)__shfl_xor((int)cnt, 1, 64);
+        const uint32_t pair = cnt + c1;
+        const uint32_t c2 = (uint32_t)__shfl_xor((int)pair, 2, 64);
+        const uint32_t live = pair + c2;
+        const uint32_t before = ((q & 1) ? c1 : 0u) + ((q & 2) ? c2 : 0u);
+        int last = max(top, __shfl_xor(top, 1, 64));
+        last = max(last, __shfl_xor(last, 2, 64));
+        const uint32_t PT = (live + (uint32_t)BATCH - 1u) & ~((uint32_t)BATCH - 1u);
+        uint32_t incl = q == 0 ? PT : 0u;   // the first lane of a step carries its padded length
 #pragma unroll
-        for (int d = 1; d < SEG; d <<= 1) {
+        for (int d = 1; d < HSEG; d <<= 1) {
             const uint32_t o = __shfl_up(incl, d, 64);
-            if (wi >= d) incl += o;
+            if (hi >= d) incl += o;
         }
-        const uint32_t step_start = incl - PT;   // both lanes of a step see the same inclusive sum
-        lpos = step_start + ((wi & 1) ? ocnt : 0u);
+        const uint32_t step_start = incl - PT;   // all lanes of a step see the same inclusive sum
+        lpos = step_start + before;
         ltot = live;
         uint8_t *lst = &lists[wave][g * REGION];
         uint8_t *dst = lst + lpos;
-        const uint32_t half = (uint32_t)(wi & 1) * 64u;
-        while (m != 0) {   // as many rounds as the fullest word of the wave has bits
-            *dst++ = (uint8_t)(half + (uint32_t)__ffsll((unsigned long long)m) - 1u);
+        const uint32_t base = (uint32_t)q * 32u;
+        while (m != 0) {   // as many rounds as the fullest half word of the wave has bits
+            *dst++ = (uint8_t)(base + (uint32_t)__ffs((int)m) - 1u);
             m &= m - 1;
         }
-        if ((wi & 1) && live != 0) {
-            const uint8_t last = (uint8_t)(cnt ? top : otop);
-            for (uint32_t i = live; i < PT; ++i) lst[step_start + i] = last;
-        }
+        if (q == 3 && live != 0)
+            for (uint32_t i = live; i < PT; ++i) lst[step_start + i] = (uint8_t)last;
     };
     // first list slot and number of live k of step ci for group g
     auto step_range = [&](int ci, int g, int &start, int &n) __attribute__((always_inline)) {
-        start = (int)__builtin_amdgcn_readlane(lpos, g * SEG + ci * WPC);
-        n = (int)__builtin_amdgcn_readlane(ltot, g * SEG + ci * WPC);
+        start = (int)__builtin_amdgcn_readlane(lpos, g * HSEG + ci * 4);
+        n = (int)__builtin_amdgcn_readlane(ltot, g * HSEG + ci * 4);
     };
 
     // B operands.  Every load is in bounds: list slots past a step's last quad are not read (the
