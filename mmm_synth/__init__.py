@@ -168,6 +168,30 @@ def relu_mlp(tokens: int, d_ff: int, d_model: int, bw: int, mu: float, p_rows: O
     return w
 
 
+def column_sparse(M: int, K: int, N: int, bw: int, p_cols: float, p_in: float, p_blocks: float, seed: int,
+                  name: Optional[str] = None, dtype: int = DT_F32) -> Workload:
+    """Column-structured A (the random-column form of the paper's Fig. "Matrix forms"): a set of columns of X, each
+    chosen with probability p_cols, is switched on, the same set of rows of Y is switched on (the contextual selection
+    of neurons of an MLP), elements inside a kept column survive with probability p_in, blocks inside a kept row of Y
+    with probability p_blocks.  Draw order: X, Y, column uniforms, element uniforms, block uniforms."""
+    assert N % bw == 0
+    rng = np.random.Generator(np.random.PCG64(seed))
+    X = _values(rng, (M, K), "normal", 0.0, 1.0)
+    Y = _values(rng, (K, N), "normal", 0.0, 1.0)
+    cols = rng.random(size=(K,), dtype=np.float32) < np.float32(p_cols)
+    ue = rng.random(size=(M, K), dtype=np.float32)
+    ub = rng.random(size=(K, N // bw), dtype=np.float32)
+    w = Workload(name=name or f"colsparse_{M}x{K}x{N}_c{int(round(p_cols * 100))}_bw{bw}", M=M, K=K, N=N, bw=bw,
+                 dtype=dtype, X=X, Y=Y, pred=PRED_NONZERO, threshold=0.0,
+                 keep_a=pack_bits((ue < np.float32(p_in)) & cols[None, :]), keep_rows=pack_bits(cols)[0],
+                 keep_blocks=pack_bits(ub < np.float32(p_blocks)), p_a=p_cols * p_in, p_b=p_cols * p_blocks,
+                 seed=seed, meta={"p_cols": p_cols})
+    if dtype == DT_BF16:
+        w.X_bits, w.X = round_to_bf16(w.X)
+        w.Y_bits, w.Y = round_to_bf16(w.Y)
+    return w
+
+
 SWEEP_P = (0.40, 0.30, 0.20, 0.10, 0.05)
 
 

@@ -124,6 +124,16 @@ def test_long_k_dense_lists(variant, bw, p_a, p_b):
     check_workload(w, f"long K variant {variant} bw {bw}", exact=True)
 
 
+@pytest.mark.parametrize("bw", [8, 16, 32])
+def test_column_structured_a(bw):
+    """Whole columns of A and the same rows of B switched off: the k lists shrink to the shared set."""
+    w = synth.column_sparse(130, 1000, 320, bw, 0.15, 0.7, 0.8, 600 + bw)
+    run, (ab, bb, *_rest) = check_workload(w, f"column sparse bw {bw}")
+    selected = synth.unpack_bits(w.keep_rows.reshape(1, -1), w.K)[0]
+    assert not (synth.unpack_bits(ab, w.K).any(axis=0) & ~selected).any()
+    assert not (synth.unpack_bits(bb, w.N // bw).any(axis=1) & ~selected).any()
+
+
 def test_padded_leading_dimensions_and_unaligned_rows():
     w = synth.random_masked(70, 203, 80, 16, 0.3, 0.5, 31, dist="smallint")
     check_workload(w, "ld padded", exact=True, ldx=209, ldy=83, ldc=91)
