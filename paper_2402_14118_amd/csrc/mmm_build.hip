@@ -37,7 +37,7 @@ struct BuildParams {
     const uint64_t *keep_rows;
     const uint64_t *keep_blocks;
     uint64_t *b_bits;
-    uint16_t *bt16;
+    uint16_t *bt_pieces;   // the transposed B map seen as pieces of MMM_BT_PIECE bits
     int64_t M, K, N, NB, WA, WB, MT, KBA;
     uint32_t thr_bits;
     int32_t pred;
@@ -171,7 +171,8 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
 
 // ---- B side: one workgroup = 16 rows (values of k) x 64 blocks -------------------------------
 template <typename T, int BW>
-__device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int lane, int wave, uint32_t *pieces)
+__device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int lane, int wave, uint32_t *pieces,
+                                       uint8_t (*gpos)[B_ROWS_PER_WAVE][64], uint64_t (*gword)[B_ROWS_PER_WAVE])
 {
     constexpr int BPL = 64 / BW;   // blocks covered by one 64-lane load
     const int64_t piece = bb / p.WB, w = bb % p.WB;
@@ -200,24 +201,55 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
         uint64_t word = 0;
         if (kept[r] != 0) {
             const T *row = Y + k * p.ldy + w * 64 * BW;
-            uint64_t mine = 0;
-#pragma unroll
-            for (int j0 = 0; j0 < BW; j0 += PER) {
-                uint32_t u[PER];
-#pragma unroll
-                for (int j = 0; j < PER; ++j) {
-                    const int blk = (j0 + j) * BPL + lane / BW;   // block (inside this word) of this lane's element
-                    u[j] = 0;
-                    if ((kept[r] >> blk) & 1ull) u[j] = f32_bits<T>(row[(j0 + j) * 64 + lane]);
-                }
-#pragma unroll
-                for (int j = 0; j < PER; ++j) {
-                    const uint64_t m = ballot64((u[j] & 0x7fffffffu) != 0);
-                    if (lane / BPL == j0 + j) mine = m;   // lane L collects the load that holds block L
-                }
-            }
             const uint64_t bwmask = BW == 32 ? 0xffffffffull : ((1ull << BW) - 1ull);
-            word = ballot64(((mine >> ((lane % BPL) * BW)) & bwmask) != 0);
+            constexpr int ROUNDS = 4;   // gather path: at most ROUNDS loads of BPL kept blocks each
+            const int nkept = __popcll(kept[r]);
+            if (nkept <= ROUNDS * BPL) {
+                // Few blocks are switched on: their positions are compacted into a short list (lane b
+                // writes b at the rank of bit b), and one load fetches BPL listed blocks, wherever
+                // they are.  The list and the result word are private to the wave and the row; LDS
+                // executes the wave's accesses in order.
+                uint8_t *plist = gpos[wave][r];
+                uint64_t *res = &gword[wave][r];
+                if ((kept[r] >> lane) & 1ull) plist[mbcnt64(kept[r])] = (uint8_t)lane;
+                if (lane == 0) *res = 0;
+                const int slot = lane / BW;   // which of the load's blocks this lane reads
+                uint32_t u[ROUNDS];
+                int pos[ROUNDS];
+#pragma unroll
+                for (int t = 0; t < ROUNDS; ++t) {
+                    const int j = t * BPL + slot;
+                    pos[t] = j < nkept ? (int)plist[j] : -1;
+                    u[t] = 0;
+                    if (pos[t] >= 0) u[t] = f32_bits<T>(row[pos[t] * BW + lane % BW]);
+                }
+#pragma unroll
+                for (int t = 0; t < ROUNDS; ++t) {
+                    if (t * BPL >= nkept) break;   // wave-uniform
+                    const uint64_t m = ballot64((u[t] & 0x7fffffffu) != 0);
+                    if (lane % BW == 0 && pos[t] >= 0 && ((m >> (slot * BW)) & bwmask) != 0)
+                        __hip_atomic_fetch_or(res, 1ull << pos[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+                word = *res;
+            } else {
+                uint64_t mine = 0;
+#pragma unroll
+                for (int j0 = 0; j0 < BW; j0 += PER) {
+                    uint32_t u[PER];
+#pragma unroll
+                    for (int j = 0; j < PER; ++j) {
+                        const int blk = (j0 + j) * BPL + lane / BW;   // block (inside this word) of this lane's element
+                        u[j] = 0;
+                        if ((kept[r] >> blk) & 1ull) u[j] = f32_bits<T>(row[(j0 + j) * 64 + lane]);
+                    }
+#pragma unroll
+                    for (int j = 0; j < PER; ++j) {
+                        const uint64_t m = ballot64((u[j] & 0x7fffffffu) != 0);
+                        if (lane / BPL == j0 + j) mine = m;   // lane L collects the load that holds block L
+                    }
+                }
+                word = ballot64(((mine >> ((lane % BPL) * BW)) & bwmask) != 0);
+            }
         }
         if (k < p.K && lane == 0) p.b_bits[k * p.WB + w] = word;
         piece_bits |= (uint32_t)((word >> lane) & 1ull) << (wave * B_ROWS_PER_WAVE + r);
@@ -228,7 +260,7 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
         uint32_t v = 0;
         for (int w = 0; w < BUILD_WAVES; ++w) v |= pieces[w * 64 + lane];
         const int64_t blk = w * 64 + lane;
-        if (blk < p.NB) p.bt16[blk * (p.WA * 4) + piece] = (uint16_t)v;
+        if (blk < p.NB) p.bt_pieces[blk * (p.WA * (64 / MMM_BT_PIECE)) + piece] = (uint16_t)v;
     }
 }
 
@@ -238,6 +270,8 @@ __global__ __launch_bounds__(BUILD_THREADS) void mmm_build_kernel(const BuildPar
     __shared__ uint64_t red[BUILD_WAVES * A_WORDS];
     __shared__ uint32_t tot[BUILD_WAVES];
     __shared__ uint32_t pieces[BUILD_WAVES * 64];
+    __shared__ uint8_t gpos[BUILD_WAVES][B_ROWS_PER_WAVE][64];   // B side: positions of the kept blocks of a row word
+    __shared__ uint64_t gword[BUILD_WAVES][B_ROWS_PER_WAVE];     // B side: occupancy word gathered from them
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t b = blockIdx.x;
@@ -251,11 +285,11 @@ __global__ __launch_bounds__(BUILD_THREADS) void mmm_build_kernel(const BuildPar
     } else {
         const int64_t bw = p.N / p.NB;
         if (bw == 8)
-            scan_b<T, 8>(p, b - p.n_a, lane, wave, pieces);
+            scan_b<T, 8>(p, b - p.n_a, lane, wave, pieces, gpos, gword);
         else if (bw == 16)
-            scan_b<T, 16>(p, b - p.n_a, lane, wave, pieces);
+            scan_b<T, 16>(p, b - p.n_a, lane, wave, pieces, gpos, gword);
         else
-            scan_b<T, 32>(p, b - p.n_a, lane, wave, pieces);
+            scan_b<T, 32>(p, b - p.n_a, lane, wave, pieces, gpos, gword);
     }
 }
 
@@ -299,6 +333,8 @@ __global__ __launch_bounds__(256) void mmm_stats_kernel(const uint64_t *a_bits, 
 // What keep_element compares against.  GT: x > t  <=>  key(x) > key(t) on the order-preserving key
 // (both zeros map to the same key).  ABS_GT: |x| > t; a negative t passes every non-zero x (magnitude
 // bits of x > 0), t = -0 is t = 0.  A NaN threshold passes nothing (nothing exceeds 0xffffffff).
+static_assert(MMM_BT_PIECE == 16, "pieces of the transposed map are stored as 16-bit words");
+
 static uint32_t threshold_key(int32_t pred, float threshold)
 {
     union { float f; uint32_t u; } cv;
@@ -329,7 +365,7 @@ hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStrea
     p.keep_rows = a.keep_rows;
     p.keep_blocks = a.keep_blocks;
     p.b_bits = m->b_bits;
-    p.bt16 = reinterpret_cast<uint16_t *>(m->bt_bits);
+    p.bt_pieces = reinterpret_cast<uint16_t *>(m->bt_bits);
     p.M = m->M;
     p.K = m->K;
     p.N = m->N;
