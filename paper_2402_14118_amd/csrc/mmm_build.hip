@@ -12,8 +12,8 @@
 // transposed to one bit-row per block column.
 //
 // One launch covers both matrices: the first n_a workgroups scan X, the rest
-// scan Y.  Every output word has exactly one producer, so there are no atomics
-// and nothing needs clearing beforehand.
+// scan Y.  Every output word in device memory has exactly one producer, so no
+// global atomics are used and nothing needs clearing beforehand.
 #include "mmm_internal.h"
 
 namespace {

@@ -26,23 +26,24 @@
 // Pipeline: list entries travel into registers two steps before they are
 // added, the first B operands of a step are requested one step ahead, and inside
 // a long k list the B operands of the next batch are requested before the
-// current batch is multiplied.  The map words a workgroup needs are copied to
-// LDS, and expanded to k lists, in windows of several steps.  The kernel is
-// bound by instruction issue and latency rather than by any pipe, so the
-// workgroup shapes that do best are those that put sixteen waves on a compute
-// unit (eight or sixteen waves per workgroup, one 16-column group per wave).
+// current batch is multiplied.  Every lane fetches half a map word of its
+// wave's column group and expands it into the k lists, in windows of several
+// steps.  The kernel is bound by instruction issue on the SIMDs (an fp32 MFMA
+// and a vector instruction do not run side by side there), so it is written to
+// need few instructions per MFMA, and the workgroup shapes that do best are
+// those that put sixteen waves on a compute unit (eight or sixteen waves per
+// workgroup, one 16-column group per wave).
 #include "mmm_internal.h"
 
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 constexpr int TM = MMM_AB_ROWS;   // rows of C per workgroup = rows of a block of A
 constexpr int KC = MMM_AB_COLS;   // k per step = columns of a block of A
 constexpr int WPC = KC / 64;      // map words per step
 constexpr int QB = 4;             // k-list quads per batch
-constexpr int BATCH = 4 * QB;      // list slots per batch (a power of two that divides KC)
+constexpr int BATCH = 4 * QB;     // list slots per batch (a power of two that divides KC)
 constexpr int SLAB = MMM_SLAB_FLOATS;                 // floats per slab
 constexpr uint32_t SLAB_BYTES = (uint32_t)SLAB * 4u;
 constexpr uint32_t COLB = MMM_SLAB_COL_BYTES;         // bytes per slab column; column KC stays zero
@@ -62,7 +63,7 @@ struct MatmulParams {
     int64_t M, K, N, NB, WA, WB, MT, KBA;
     int32_t bw;
     int32_t tiles_m, tiles_n, split_k, chunks_total, chunks_per_split;
-    int32_t window_chunks;   // steps whose map words are held in LDS (and whose k lists exist) at a time
+    int32_t window_chunks;   // steps whose k lists are built in one go
     int32_t zero;            // always 0
     int32_t accumulate;
 };
@@ -81,7 +82,7 @@ __device__ __forceinline__ uint32_t xcd_contiguous_id(uint32_t b, uint32_t n)
     return x * q + (x < rem ? x : rem) + i;
 }
 
-// map words one wave expands into k lists per window (fewer for the larger workgroups, whose
+// map words one wave expands into k lists per window (fewer for the eight-wave workgroups, whose
 // lists would otherwise keep a second workgroup off the compute unit)
 constexpr int list_words(int nw) { return nw == 8 ? 16 : 32; }
 
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     constexpr int EPT = 1024 / NT;    // list entries of A per thread and round
     constexpr int ROUND = NT * EPT;   // list entries one round of the workgroup moves
     constexpr int LW = list_words(NW);
-    constexpr int SEG = LW / GW;      // lanes (= map words) per group: SEG / WPC steps per window
+    constexpr int SEG = LW / GW;      // map words per group and window: SEG / WPC steps
     constexpr int REGION = SEG * 64;  // list bytes per group: the worst case
     constexpr uint32_t ESZ = (uint32_t)sizeof(T);
     typedef float avec __attribute__((ext_vector_type(RT)));   // A operands of the RT row tiles for one k
