@@ -229,6 +229,34 @@ def test_accumulate_and_cached_b_map():
     np.testing.assert_array_equal(run.C.cpu().numpy(), C2_ref)
 
 
+@pytest.mark.parametrize("variant", [0, 1, 5])
+def test_accumulate_with_split_k_and_padded_c(variant):
+    """C += A x B through the split-K path (partials reduced, then added), rows of C padded: the padding stays."""
+    mm.mmm_set_option("matmul_variant", variant)
+    mm.mmm_set_option("split_k", 3)
+    short = mm.mmm_matmul_variant_name(variant).startswith("R2")
+    w = synth.random_masked(30 if short else 90, 900, 176, 16, 0.3, 0.3, 23 + variant, dist="smallint")
+    _, _, C_ref, _ = oracle.run_workload(w)
+    run = HipRun(w, ldc=w.N + 5)
+    run.build()
+    run.matmul()
+    run.matmul(accumulate=True)
+    run.matmul(accumulate=True)
+    torch.cuda.synchronize()
+    assert run.eng.plan()[1] == 3
+    np.testing.assert_array_equal(run.C.cpu().numpy(), 3 * C_ref)
+    assert torch.isnan(run.Cbuf[:, w.N:]).all()
+
+
+@pytest.mark.parametrize("variant", range(mm.mmm_matmul_variant_count()))
+def test_bf16_every_variant(variant):
+    mm.mmm_set_option("matmul_variant", variant)
+    mm.mmm_set_option("split_k", 1)
+    short = mm.mmm_matmul_variant_name(variant).startswith("R2")
+    w = synth.random_masked(30 if short else 100, 1500, 160, 32, 0.3, 0.4, 300 + variant, dist="smallint", dtype=synth.DT_BF16)
+    check_workload(w, f"bf16 variant {variant}", exact=True)
+
+
 def test_run_to_run_bitwise_reproducible():
     w = synth.config(2, scale=4)
     run = HipRun(w)
