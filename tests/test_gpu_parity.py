@@ -277,6 +277,36 @@ def test_bf16_small():
     check_workload(w, "bf16 int", exact=True)
 
 
+def test_random_shapes_sweep():
+    """Many small random cases (shape, block width, densities, dtype, variant, split, leading dimensions), exact on
+    integer inputs; each case is printed before it runs."""
+    rng = np.random.default_rng(2024)
+    nv = mm.mmm_matmul_variant_count()
+    for it in range(250):
+        bw = int(rng.choice([8, 16, 32]))
+        M, K, N = int(rng.integers(1, 200)), int(rng.integers(1, 3000)), bw * int(rng.integers(1, 40))
+        if rng.random() < 0.3:
+            M = int(rng.integers(1, 33))
+        p_a, p_b = (float(rng.choice([0.02, 0.1, 0.3, 0.7, 1.0])) for _ in range(2))
+        dtype = int(rng.choice([synth.DT_F32, synth.DT_BF16]))
+        variant, split = int(rng.integers(-1, nv)), int(rng.integers(0, 5))
+        if variant >= 0 and mm.mmm_matmul_variant_name(variant).startswith("R2") and M > 32:
+            variant = -1
+        ld = dict(ldx=K + int(rng.integers(0, 9)), ldy=N + int(rng.integers(0, 9)), ldc=N + int(rng.integers(0, 9)))
+        what = f"sweep {it}: M={M} K={K} N={N} bw={bw} p_a={p_a} p_b={p_b} dtype={dtype} variant={variant} split={split} {ld}"
+        print(what, flush=True)
+        mm.mmm_set_option("matmul_variant", variant)
+        mm.mmm_set_option("split_k", split)
+        w = synth.random_masked(M, K, N, bw, p_a, p_b, 20000 + it, dist="smallint", dtype=dtype)
+        ab, bb, C_ref, _ = oracle.run_workload(w)
+        run = HipRun(w, **ld)
+        a_hip, b_hip, C = run.run()
+        np.testing.assert_array_equal(a_hip, ab, err_msg=what)
+        np.testing.assert_array_equal(b_hip, bb, err_msg=what)
+        np.testing.assert_array_equal(C, C_ref, err_msg=what)
+        assert torch.isnan(run.Cbuf[:, N:]).all(), what
+
+
 # ---- the benchmark configurations at full size ------------------------------------------------
 def test_config1_full():
     check_workload(synth.config(1), "config 1")
