@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--split-k", type=int, default=0)
+    ap.add_argument("--cold-sets", type=int, default=0,
+                    help="also time the steps over this many separate copies of all buffers used in turn (enough "
+                         "copies to exceed the 256 MB of last-level cache give the cold-cache step time)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 64 MiB device copy a few times, so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic")
@@ -129,6 +132,34 @@ def main():
     matmul_ms = np.array([ev[i][1].elapsed_time(ev[i][2]) for i in range(K)])
     t_build, t_matmul = float(build_ms.mean()), float(matmul_ms.mean())
 
+    cold_ms = None
+    if args.cold_sets > 1:
+        # the same K steps over several copies of every buffer, used in turn: what the caches hold is stale
+        sets = []
+        for _ in range(args.cold_sets):
+            e = mm.MaskedMatmul(w.M, w.K, w.N, w.bw, w.dtype)
+            sets.append((e, X.clone(), Y.clone(), torch.empty_like(C),
+                         None if keep_a is None else keep_a.clone(),
+                         None if keep_rows is None else keep_rows.clone(),
+                         None if keep_blocks is None else keep_blocks.clone()))
+
+        def cold_step(i):
+            e, Xs, Ys, Cs, ka, kr, kb = sets[i % len(sets)]
+            e.build_maps(Xs, Ys, w.pred, w.threshold, ka, kr, kb)
+            e.matmul(Xs, Ys, Cs)
+
+        for i in range(len(sets)):
+            cold_step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(K):
+            cold_step(i)
+        torch.cuda.synchronize()
+        cold_ms = (time.perf_counter() - t0) * 1e3 / K
+        bytes_per_set = sum(t.numel() * t.element_size() for t in sets[0][1:] if t is not None) + sets[0][0].workspace.numel()
+        cold_info = {"sets": len(sets), "bytes_per_set": bytes_per_set, "ms_per_step": cold_ms}
+        del sets
+
     useful_flops = 2.0 * useful_macs
     dense_flops = 2.0 * w.M * w.K * w.N
     value = useful_flops / (ms_per_step * 1e-3) / 1e9
@@ -187,6 +218,8 @@ def main():
         "kernel_timing": "second pass of the same steps with a HIP event after every launch",
         "roofline": roofline,
     }
+    if cold_ms is not None:
+        out["cold_cache"] = cold_info
 
     if not args.no_dense:
         # comparison point only: a dense GEMM of the materialised masked operands, same dtype
