@@ -35,7 +35,7 @@ bool shape_ok(int64_t M, int64_t K, int64_t N, int32_t bw)
     if (M < 1 || K < 1 || N < 1) return false;
     if (bw != 8 && bw != 16 && bw != 32) return false;
     if (N % bw != 0) return false;
-    // 31-bit grids and 16-bit chunk-relative indices are used throughout
+    // 31-bit grids and 32-bit tile-relative offsets are used throughout
     if (M > (1LL << 30) || K > (1LL << 30) || N > (1LL << 30)) return false;
     return true;
 }
