@@ -181,18 +181,24 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
     const int64_t nb_left = p.NB - w * 64;
     const uint64_t valid = nb_left >= 64 ? ~0ull : ((1ull << nb_left) - 1ull);
     uint32_t piece_bits = 0;
-    // which blocks of the wave's rows the keep bitmaps leave switched on: asked for all rows first,
-    // so that the waits for these small loads overlap
+    // which blocks of the wave's rows the keep bitmaps leave switched on: lane r fetches the two
+    // keep words of row r, so that all of them are in flight together
+    uint64_t krw = ~0ull, kbw = ~0ull;
+    {
+        const int64_t kl = kbase + lane;
+        const bool mine = lane < B_ROWS_PER_WAVE && kl < p.K;
+        if (p.keep_rows != nullptr && mine) krw = p.keep_rows[kl >> 6];
+        if (p.keep_blocks != nullptr && mine) kbw = p.keep_blocks[kl * p.WB + w];
+    }
     uint64_t kept[B_ROWS_PER_WAVE];
 #pragma unroll
     for (int r = 0; r < B_ROWS_PER_WAVE; ++r) {
         const int64_t k = kbase + r;
-        kept[r] = 0;
-        if (k < p.K) {
-            kept[r] = valid;
-            if (p.keep_rows != nullptr) kept[r] &= 0ull - ((p.keep_rows[k >> 6] >> (k & 63)) & 1ull);
-            if (p.keep_blocks != nullptr) kept[r] &= p.keep_blocks[k * p.WB + w];
-        }
+        const uint64_t kr = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(krw >> 32), r) << 32) |
+                            (uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)krw, r);
+        const uint64_t kb = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(kbw >> 32), r) << 32) |
+                            (uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)kbw, r);
+        kept[r] = k < p.K ? valid & kb & (0ull - ((kr >> (k & 63)) & 1ull)) : 0ull;
     }
     constexpr int PER = BW <= 16 ? BW : 16;   // loads in flight per lane and row
 #pragma unroll
