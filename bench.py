@@ -26,9 +26,11 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 
 def parse_workload(name):
     import mmm_synth as synth
-    if name.startswith("cfg3"):
-        ip = int(name.split(":")[1]) if ":" in name else 3
-        return synth.config(3, ip)
+    if name.startswith("cfg3"):       # cfg3:<i> = diagonal point i of the sweep; cfg3:<ia>:<ib> = keep index of A, of B
+        f = name.split(":")
+        ia = int(f[1]) if len(f) > 1 else 3
+        ib = int(f[2]) if len(f) > 2 else ia
+        return synth.config(3, ia, ib)
     if name == "colsparse":   # beyond the five configurations: column-structured A, MLP down-projection shape
         return synth.column_sparse(2048, 16384, 4096, 32, 0.1, 1.0, 1.0, 2001)
     return synth.config(int(name[3:]))
@@ -39,7 +41,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", help="cfg1 | cfg2 | cfg3:<0..4> | cfg4 | cfg5 | colsparse")
+    ap.add_argument("--workload", default="cfg2", help="cfg1 | cfg2 | cfg3:<0..4>[:<0..4>] | cfg4 | cfg5 | colsparse")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--variant", type=int, default=-1)
