@@ -183,6 +183,15 @@ mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt,
  * Errors: MMM_ERR_INVALID_ARG (unknown name or value out of range). */
 mmm_status mmm_set_option(const char *name, int64_t value);
 
+/* Fix the launch plan of one handle: tile variant (-1 = leave it to the options
+ * above / the automatic choice) and number of K splits (0 = likewise).  A
+ * variant that computes too few rows for the matrix, or more splits than K has
+ * steps or the workspace has room for, is adjusted as in the automatic choice;
+ * mmm_matmul_plan reports what will be used.  This is the tuning knob the paper
+ * leaves to an autotuner (section 3, "Optimizations": the base vector multiple).
+ * Errors: MMM_ERR_INVALID_ARG (maps NULL, values out of range). */
+mmm_status mmm_maps_set_plan(mmm_maps *maps, int32_t variant, int32_t split_k);
+
 /* Number of compiled tile variants and a short description of variant i
  * (NULL if i is out of range). */
 int32_t mmm_matmul_variant_count(void);

@@ -27,7 +27,7 @@ MMM_PRED_NONZERO, MMM_PRED_GT, MMM_PRED_ABS_GT = 0, 1, 2
 EXPORTS = [
     "mmm_maps_workspace_bytes", "mmm_maps_init", "mmm_maps_release", "mmm_build_maps", "mmm_maps_view",
     "mmm_maps_view_derived", "mmm_maps_view_lists", "mmm_maps_stats", "mmm_matmul", "mmm_set_option", "mmm_matmul_variant_count",
-    "mmm_matmul_variant_name", "mmm_matmul_plan", "mmm_status_string", "mmm_last_device_error",
+    "mmm_matmul_variant_name", "mmm_matmul_plan", "mmm_maps_set_plan", "mmm_status_string", "mmm_last_device_error",
 ]
 
 
@@ -65,6 +65,7 @@ def _load() -> ctypes.CDLL:
     lib.mmm_maps_stats.argtypes = [vp, c.POINTER(c.c_uint64), c.POINTER(c.c_uint64), c.POINTER(c.c_uint64), vp]
     lib.mmm_matmul.argtypes = [vp, i32, vp, i64, vp, i64, vp, i64, i32, vp]
     lib.mmm_set_option.argtypes = [c.c_char_p, i64]
+    lib.mmm_maps_set_plan.argtypes = [vp, i32, i32]
     lib.mmm_matmul_variant_count.restype = i32
     lib.mmm_matmul_variant_name.argtypes = [i32]
     lib.mmm_matmul_variant_name.restype = c.c_char_p
@@ -169,6 +170,10 @@ def mmm_maps_stats(maps: int, stream=None):
 def mmm_matmul(maps: int, dt: int, X, ldx: int, Y, ldy: int, C, ldc: int, accumulate: int = 0, stream=None) -> None:
     _check(lib.mmm_matmul(maps, dt, _ptr(X), ldx, _ptr(Y), ldy, _ptr(C), ldc, int(accumulate), _stream(stream)),
            "mmm_matmul")
+
+
+def mmm_maps_set_plan(maps: int, variant: int = -1, split_k: int = 0) -> None:
+    _check(lib.mmm_maps_set_plan(maps, int(variant), int(split_k)), "mmm_maps_set_plan")
 
 
 def mmm_set_option(name: str, value: int) -> None:

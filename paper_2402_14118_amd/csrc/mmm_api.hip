@@ -77,7 +77,7 @@ mmm_plan make_plan(const mmm_maps *m, int32_t dt)
 {
     (void)dt;
     mmm_plan p{};
-    int64_t v = g_opt_variant.load();
+    int64_t v = m->plan_variant >= 0 ? m->plan_variant : g_opt_variant.load();
     if (v >= 0 && v < mmm_variant_count() && mmm_variant((int32_t)v).rows < MMM_AB_ROWS && m->M > mmm_variant((int32_t)v).rows)
         v = -1;   // that kernel computes too few rows for this matrix
     if (v < 0 || v >= mmm_variant_count()) {
@@ -97,7 +97,7 @@ mmm_plan make_plan(const mmm_maps *m, int32_t dt)
     p.tiles_n = (int32_t)((m->N + vi.TN - 1) / vi.TN);
     p.chunks_total = (int32_t)((m->K + vi.KC - 1) / vi.KC);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-    int64_t split = g_opt_split.load();
+    int64_t split = m->plan_split > 0 ? m->plan_split : g_opt_split.load();
     if (split <= 0) {
         split = 1;
         if (tiles < 256) split = (512 + tiles - 1) / tiles;   // fewer tiles than CUs: split K to give every CU work
@@ -174,6 +174,8 @@ mmm_status mmm_maps_init(void *dev_workspace, size_t workspace_bytes, int64_t M,
     m->ws_bytes = workspace_bytes;
     m->a_built = m->b_built = false;
     m->a_dtype = m->b_dtype = -1;
+    m->plan_variant = -1;
+    m->plan_split = 0;
     *out = m;
     return MMM_OK;
 }
@@ -312,6 +314,16 @@ mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t
         note_device_error("masked GEMM launch", e);
         return MMM_ERR_DEVICE;
     }
+    return MMM_OK;
+}
+
+mmm_status mmm_maps_set_plan(mmm_maps *maps, int32_t variant, int32_t split_k)
+{
+    if (maps == nullptr) return MMM_ERR_INVALID_ARG;
+    if (variant < -1 || variant >= mmm_variant_count()) return MMM_ERR_INVALID_ARG;
+    if (split_k < 0 || split_k > 4096) return MMM_ERR_INVALID_ARG;
+    maps->plan_variant = variant;
+    maps->plan_split = split_k;
     return MMM_OK;
 }
 

@@ -53,6 +53,8 @@ struct mmm_maps {
     // state
     bool a_built, b_built;
     int32_t a_dtype, b_dtype;
+    // launch plan fixed for this handle (-1 / 0: none, follow the process-wide options)
+    int32_t plan_variant, plan_split;
 };
 
 struct mmm_build_args {

@@ -55,6 +55,33 @@ class MaskedMatmul:
     def plan(self):
         return B.mmm_matmul_plan(self.maps, self.dtype)
 
+    def set_plan(self, variant: int = -1, split_k: int = 0) -> None:
+        B.mmm_maps_set_plan(self.maps, variant, split_k)
+
+    def autotune(self, X: torch.Tensor, Y: torch.Tensor, C: torch.Tensor, splits=(0,), reps: int = 20):
+        """Time every tile variant (and the given K splits) on the maps as built, with the caller's operands, and fix
+        the fastest as this handle's plan.  Returns [(microseconds, variant, split_k)] sorted by time.  C is
+        overwritten."""
+        results = []
+        for v in range(B.mmm_matmul_variant_count()):
+            for sp in splits:
+                self.set_plan(v, sp)
+                pv, ps, _ = self.plan()
+                if pv != v or any(r[1] == pv and r[2] == ps for r in results):
+                    continue   # not usable for this shape, or the same plan as one already timed
+                for _ in range(3):
+                    self.matmul(X, Y, C)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    self.matmul(X, Y, C)
+                e1.record()
+                torch.cuda.synchronize()
+                results.append((e0.elapsed_time(e1) * 1e3 / reps, pv, ps))
+        results.sort()
+        self.set_plan(results[0][1], results[0][2])
+        return results
+
     def _bits_tensor(self, addr: int, rows: int, words: int) -> torch.Tensor:
         off = addr - self.workspace.data_ptr()
         assert 0 <= off and off + rows * words * 8 <= self.workspace.numel()

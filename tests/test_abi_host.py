@@ -80,6 +80,20 @@ def test_init_and_call_validation_without_device():
         assert a < ca < b < bt and kw == 2
         v, s, wg = mm.mmm_matmul_plan(maps, 0)
         assert 0 <= v < mm.mmm_matmul_variant_count() and s >= 1 and wg >= 1
+        # a plan fixed for the handle wins over the automatic choice; what cannot be used is adjusted
+        nv = mm.mmm_matmul_variant_count()
+        assert L.mmm_maps_set_plan(maps, nv, 0) == B.MMM_ERR_INVALID_ARG
+        assert L.mmm_maps_set_plan(maps, 0, -1) == B.MMM_ERR_INVALID_ARG
+        assert L.mmm_maps_set_plan(None, 0, 1) == B.MMM_ERR_INVALID_ARG
+        for cand in range(nv):
+            mm.mmm_maps_set_plan(maps, cand, 1)
+            v2, s2, _ = mm.mmm_matmul_plan(maps, 0)
+            short = mm.mmm_matmul_variant_name(cand).startswith("R2")   # 32-row kernels cannot serve M = 64
+            assert s2 == 1 and ((v2 == cand) != short)
+        mm.mmm_maps_set_plan(maps, 0, 4096)
+        assert mm.mmm_matmul_plan(maps, 0)[1] == 1        # K = 128 is a single step: nothing to split
+        mm.mmm_maps_set_plan(maps)
+        assert mm.mmm_matmul_plan(maps, 0)[:2] == (v, s)
     finally:
         mm.mmm_maps_release(maps)
     mm.mmm_maps_release(None)

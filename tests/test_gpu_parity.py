@@ -257,6 +257,20 @@ def test_bf16_every_variant(variant):
     check_workload(w, f"bf16 variant {variant}", exact=True)
 
 
+def test_autotune_fixes_a_plan_and_keeps_the_result():
+    w = synth.random_masked(130, 900, 384, 16, 0.2, 0.2, 808, dist="smallint")
+    _, _, C_ref, _ = oracle.run_workload(w)
+    run = HipRun(w)
+    run.build()
+    timed = run.eng.autotune(run.X, run.Y, run.C, splits=(0, 2), reps=3)
+    assert len(timed) >= 4 and timed == sorted(timed)
+    assert run.eng.plan()[:2] == (timed[0][1], timed[0][2])
+    run.matmul()
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(run.C.cpu().numpy(), C_ref)
+    run.eng.set_plan()   # back to the automatic choice
+
+
 def test_run_to_run_bitwise_reproducible():
     w = synth.config(2, scale=4)
     run = HipRun(w)
