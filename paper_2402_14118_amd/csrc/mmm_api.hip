@@ -83,12 +83,14 @@ mmm_plan make_plan(const mmm_maps *m, int32_t dt)
     if (v < 0 || v >= mmm_variant_count()) {
         // automatic: the shapes that put sixteen waves on a compute unit.  32-row kernel for short
         // matrices; otherwise the 256-column tile (one workgroup of sixteen waves per CU) when that
-        // still gives every CU a workgroup, else the 128-column tile (two workgroups of eight waves)
+        // still gives every CU a workgroup, else the 128-column tile (eight waves); matrices too small
+        // to fill the machine that way, and too short in K for a split to pay, take the 64-column tile
         if (m->M <= 32) {
             v = 5;
         } else {
-            const int64_t t256 = ((m->M + 63) / 64) * ((m->N + 255) / 256);
-            v = t256 >= 256 ? 1 : 0;
+            const int64_t tm = (m->M + 63) / 64, chunks = (m->K + MMM_AB_COLS - 1) / MMM_AB_COLS;
+            const int64_t t256 = tm * ((m->N + 255) / 256), t128 = tm * ((m->N + 127) / 128);
+            v = t256 >= 256 ? 1 : (t128 >= 192 || chunks >= 16) ? 0 : 2;
         }
     }
     const mmm_variant_info &vi = mmm_variant((int32_t)v);
@@ -100,7 +102,10 @@ mmm_plan make_plan(const mmm_maps *m, int32_t dt)
     int64_t split = m->plan_split > 0 ? m->plan_split : g_opt_split.load();
     if (split <= 0) {
         split = 1;
-        if (tiles < 256) split = (512 + tiles - 1) / tiles;   // fewer tiles than CUs: split K to give every CU work
+        if (tiles < 256) {   // fewer tiles than CUs: split K to give every CU work, if every part keeps 8 steps
+            split = (512 + tiles - 1) / tiles;
+            if (split > p.chunks_total / 8) split = p.chunks_total / 8;
+        }
     }
     const int64_t max_by_ws = (int64_t)(m->partial_bytes / ((size_t)m->M * (size_t)m->N * sizeof(float)));
     if (split > max_by_ws) split = max_by_ws;
