@@ -67,12 +67,12 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     w = parse_workload(args.workload)
-    esz = 2 if w.dtype == synth.DT_BF16 else 4
+    esz = 4 if w.dtype == synth.DT_F32 else 2
 
     def up(a):
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
-    if w.dtype == synth.DT_BF16:
+    if w.dtype != synth.DT_F32:
         X, Y = up(w.X_bits.view(np.int16)), up(w.Y_bits.view(np.int16))
     else:
         X, Y = up(w.X), up(w.Y)
@@ -210,7 +210,7 @@ def main():
     out = {
         "metric": "useful_gflops", "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": K,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16" if w.dtype == synth.DT_BF16 else "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": {synth.DT_F32: "f32", synth.DT_BF16: "bf16", synth.DT_F16: "f16"}[w.dtype], "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "block_width": w.bw,
                    "nnz_a": nnz_a, "occupied_blocks_b": occ_b, "useful_macs": useful_macs,
                    "a_density": nnz_a / (w.M * w.K), "b_block_density": occ_b / (w.K * NB),
@@ -230,12 +230,18 @@ def main():
             return (((bits.unsqueeze(-1) >> sh) & 1) != 0).reshape(bits.shape[0], -1)[:, :cols]
 
         torch.cuda.synchronize()
-        Xf = X if w.dtype != synth.DT_BF16 else (X.to(torch.int32) << 16).view(torch.float32)
-        Yf = Y if w.dtype != synth.DT_BF16 else (Y.to(torch.int32) << 16).view(torch.float32)
+        def widen(t):     # device operand -> float32 values
+            if w.dtype == synth.DT_BF16:
+                return (t.to(torch.int32) << 16).view(torch.float32)
+            return t.view(torch.float16).float() if w.dtype == synth.DT_F16 else t
+
+        Xf, Yf = widen(X), widen(Y)
         A = torch.where(unpack(eng.a_bits(), w.K), Xf, torch.zeros((), device="cuda"))
         B = torch.where(unpack(eng.b_bits(), NB).repeat_interleave(w.bw, dim=1), Yf, torch.zeros((), device="cuda"))
         if w.dtype == synth.DT_BF16:
             A, B = A.bfloat16(), B.bfloat16()
+        elif w.dtype == synth.DT_F16:
+            A, B = A.half(), B.half()
         torch.backends.cuda.matmul.allow_tf32 = False
         for _ in range(5):
             D = torch.matmul(A, B)

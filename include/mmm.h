@@ -51,8 +51,10 @@ typedef enum {
     MMM_ERR_DEVICE = 6         /* a HIP call failed (launch error)                                */
 } mmm_status;
 
-/* Element type of X and Y.  BF16 is the upper half of an IEEE float. */
-typedef enum { MMM_F32 = 0, MMM_BF16 = 1 } mmm_dtype;
+/* Element type of X and Y.  BF16 is the upper half of an IEEE float, F16 the IEEE
+ * half format; both are widened to float exactly, products are accumulated in
+ * float. */
+typedef enum { MMM_F32 = 0, MMM_BF16 = 1, MMM_F16 = 2 } mmm_dtype;
 
 /* Element predicate of M.  An element of A is non-zero iff the predicate holds,
  * the optional keep bit is set, and the value is not +-0.  (Zero test by value:
@@ -145,7 +147,7 @@ mmm_status mmm_maps_view_derived(const mmm_maps *maps, const uint64_t **a_colany
  *   entries[block][*capacity] : the first counts[block] words describe those
  *       elements, each exactly once, in an order that is fixed for a given A:
  *       low 32 bits  = 272 * column_in_block + 16 * (row_in_block % 16) + 4 * (row_in_block / 16)
- *       high 32 bits = the value as IEEE float bits (bf16 widened)
+ *       high 32 bits = the value as IEEE float bits (16-bit types widened)
  *     then words {34816, 0} up to the next multiple of 64 (none if the count
  *     is one already); words beyond that are unspecified.
  * Errors: MMM_ERR_INVALID_ARG. */

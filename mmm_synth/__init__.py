@@ -28,6 +28,7 @@ PRED_ABS_GT = 2   # keep iff |x| > threshold
 
 DT_F32 = 0
 DT_BF16 = 1
+DT_F16 = 2
 
 
 def pack_bits(flags: np.ndarray) -> np.ndarray:
@@ -70,6 +71,23 @@ def round_to_bf16(x: np.ndarray):
     return bits, val
 
 
+def round_to_f16(x: np.ndarray):
+    """Round fp32 to IEEE half (nearest-even).  Returns (bits uint16, value fp32).  Input preparation only."""
+    h = np.ascontiguousarray(x, dtype=np.float32).astype(np.float16)
+    return h.view(np.uint16), h.astype(np.float32)
+
+
+def _narrow(w):
+    """Round the inputs of a workload to its 16-bit element type and keep the bit patterns."""
+    if w.dtype == DT_BF16:
+        w.X_bits, w.X = round_to_bf16(w.X)
+        w.Y_bits, w.Y = round_to_bf16(w.Y)
+    elif w.dtype == DT_F16:
+        w.X_bits, w.X = round_to_f16(w.X)
+        w.Y_bits, w.Y = round_to_f16(w.Y)
+    return w
+
+
 @dataclass
 class Workload:
     """One MMM problem instance; everything the C ABI needs, as host arrays."""
@@ -78,16 +96,16 @@ class Workload:
     K: int
     N: int
     bw: int
-    dtype: int                       # DT_F32 or DT_BF16
-    X: np.ndarray                    # fp32 [M,K]  (bf16-representable if dtype==DT_BF16)
+    dtype: int                       # DT_F32, DT_BF16 or DT_F16
+    X: np.ndarray                    # fp32 [M,K]  (representable in the 16-bit type if dtype is one)
     Y: np.ndarray                    # fp32 [K,N]
     pred: int = PRED_NONZERO
     threshold: float = 0.0
     keep_a: Optional[np.ndarray] = None       # uint64 [M, ceil(K/64)] or None
     keep_rows: Optional[np.ndarray] = None    # uint64 [ceil(K/64)] or None
     keep_blocks: Optional[np.ndarray] = None  # uint64 [K, ceil(NB/64)] or None
-    X_bits: Optional[np.ndarray] = None       # uint16 [M,K] when dtype==DT_BF16
-    Y_bits: Optional[np.ndarray] = None       # uint16 [K,N] when dtype==DT_BF16
+    X_bits: Optional[np.ndarray] = None       # uint16 [M,K] when dtype is 16-bit
+    Y_bits: Optional[np.ndarray] = None       # uint16 [K,N] when dtype is 16-bit
     p_a: float = float("nan")
     p_b: float = float("nan")
     seed: int = 0
@@ -135,10 +153,7 @@ def random_masked(M: int, K: int, N: int, bw: int, p_a: float, p_b: float, seed:
                  keep_rows=keep_rows,
                  keep_blocks=pack_bits(ub < np.float32(p_b)),
                  p_a=p_a, p_b=p_b, seed=seed)
-    if dtype == DT_BF16:
-        w.X_bits, w.X = round_to_bf16(w.X)
-        w.Y_bits, w.Y = round_to_bf16(w.Y)
-    return w
+    return _narrow(w)
 
 
 def relu_mlp(tokens: int, d_ff: int, d_model: int, bw: int, mu: float, p_rows: Optional[float],
@@ -162,10 +177,7 @@ def relu_mlp(tokens: int, d_ff: int, d_model: int, bw: int, mu: float, p_rows: O
                  keep_blocks=pack_bits(ub < np.float32(p_blocks)),
                  p_a=float("nan"), p_b=(p_rows if p_rows is not None else 1.0) * p_blocks,
                  seed=seed, meta={"mu": mu})
-    if dtype == DT_BF16:
-        w.X_bits, w.X = round_to_bf16(w.X)
-        w.Y_bits, w.Y = round_to_bf16(w.Y)
-    return w
+    return _narrow(w)
 
 
 def column_sparse(M: int, K: int, N: int, bw: int, p_cols: float, p_in: float, p_blocks: float, seed: int,
@@ -186,10 +198,7 @@ def column_sparse(M: int, K: int, N: int, bw: int, p_cols: float, p_in: float, p
                  keep_a=pack_bits((ue < np.float32(p_in)) & cols[None, :]), keep_rows=pack_bits(cols)[0],
                  keep_blocks=pack_bits(ub < np.float32(p_blocks)), p_a=p_cols * p_in, p_b=p_cols * p_blocks,
                  seed=seed, meta={"p_cols": p_cols})
-    if dtype == DT_BF16:
-        w.X_bits, w.X = round_to_bf16(w.X)
-        w.Y_bits, w.Y = round_to_bf16(w.Y)
-    return w
+    return _narrow(w)
 
 
 SWEEP_P = (0.40, 0.30, 0.20, 0.10, 0.05)

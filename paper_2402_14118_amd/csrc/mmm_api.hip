@@ -70,8 +70,8 @@ Layout make_layout(int64_t M, int64_t K, int64_t N, int32_t bw)
     return l;
 }
 
-bool dtype_ok(int32_t dt) { return dt == MMM_F32 || dt == MMM_BF16; }
-size_t elem_size(int32_t dt) { return dt == MMM_BF16 ? 2 : 4; }
+bool dtype_ok(int32_t dt) { return dt == MMM_F32 || dt == MMM_BF16 || dt == MMM_F16; }
+size_t elem_size(int32_t dt) { return dt == MMM_F32 ? 4 : 2; }
 
 mmm_plan make_plan(const mmm_maps *m, int32_t dt)
 {

@@ -46,7 +46,8 @@ struct BuildParams {
 
 template <typename T> __device__ __forceinline__ uint32_t f32_bits(T v);
 template <> __device__ __forceinline__ uint32_t f32_bits<float>(float v) { return __float_as_uint(v); }
-template <> __device__ __forceinline__ uint32_t f32_bits<uint16_t>(uint16_t v) { return (uint32_t)v << 16; }
+template <> __device__ __forceinline__ uint32_t f32_bits<uint16_t>(uint16_t v) { return (uint32_t)v << 16; }   // bf16
+template <> __device__ __forceinline__ uint32_t f32_bits<_Float16>(_Float16 v) { return __float_as_uint((float)v); }
 
 // Order-preserving key of a non-NaN float with both zeros mapped to +0.
 __device__ __forceinline__ uint32_t order_key(uint32_t u)
@@ -390,6 +391,8 @@ hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStrea
     (void)hipGetLastError();   // drop any stale error another library left on this thread
     if (a.dtype == MMM_BF16)
         hipLaunchKernelGGL(mmm_build_kernel<uint16_t>, grid, block, 0, s, p);
+    else if (a.dtype == MMM_F16)
+        hipLaunchKernelGGL(mmm_build_kernel<_Float16>, grid, block, 0, s, p);
     else
         hipLaunchKernelGGL(mmm_build_kernel<float>, grid, block, 0, s, p);
     return hipGetLastError();

@@ -70,7 +70,8 @@ struct MatmulParams {
 
 template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
-template <> __device__ __forceinline__ float to_f32<uint16_t>(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+template <> __device__ __forceinline__ float to_f32<uint16_t>(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }   // bf16
+template <> __device__ __forceinline__ float to_f32<_Float16>(_Float16 v) { return (float)v; }
 
 // Workgroups are dealt round-robin to the 8 XCDs.  Re-number them so that each
 // XCD works on a contiguous range of logical tiles: neighbours in that range
@@ -521,14 +522,15 @@ typedef void (*matmul_kernel_fn)(const MatmulParams);
 
 struct VariantEntry {
     mmm_variant_info info;
-    matmul_kernel_fn f32, bf16, f32_bw8, bf16_bw8;
+    matmul_kernel_fn f32, bf16, f16, f32_bw8, bf16_bw8, f16_bw8;
 };
 
 #define MMM_VARIANT(RT, GW, NW)                                                                             \
     {                                                                                                       \
         {"R" #RT "x16_TN" #GW "x" #NW "x16", TM, 16 * GW * NW, KC, NW * 64, NW * GW, 16 * RT},                 \
             mmm_matmul_kernel<RT, GW, NW, float, false>, mmm_matmul_kernel<RT, GW, NW, uint16_t, false>,     \
-            mmm_matmul_kernel<RT, GW, NW, float, true>, mmm_matmul_kernel<RT, GW, NW, uint16_t, true>        \
+            mmm_matmul_kernel<RT, GW, NW, _Float16, false>, mmm_matmul_kernel<RT, GW, NW, float, true>,      \
+            mmm_matmul_kernel<RT, GW, NW, uint16_t, true>, mmm_matmul_kernel<RT, GW, NW, _Float16, true>     \
     }
 
 const VariantEntry g_variants[] = {
@@ -590,7 +592,8 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtyp
     if (window > pl.chunks_per_split) window = pl.chunks_per_split;
     if (window < 1) return hipErrorInvalidValue;
     p.window_chunks = (int32_t)window;
-    matmul_kernel_fn fn = m->bw == 8 ? (dtype == MMM_BF16 ? v.bf16_bw8 : v.f32_bw8) : (dtype == MMM_BF16 ? v.bf16 : v.f32);
+    matmul_kernel_fn fn = m->bw == 8 ? (dtype == MMM_BF16 ? v.bf16_bw8 : dtype == MMM_F16 ? v.f16_bw8 : v.f32_bw8)
+                                     : (dtype == MMM_BF16 ? v.bf16 : dtype == MMM_F16 ? v.f16 : v.f32);
     (void)hipGetLastError();   // drop any stale error another library left on this thread
     hipLaunchKernelGGL(fn, dim3((uint32_t)pl.workgroups), dim3((uint32_t)v.info.threads), 0, s, p);
     hipError_t e = hipGetLastError();

@@ -6,7 +6,7 @@ import torch
 import mmm_synth as synth
 import paper_2402_14118_amd as mm
 
-TOL_REL = {synth.DT_F32: 1e-5, synth.DT_BF16: 1e-2}
+TOL_REL = {synth.DT_F32: 1e-5, synth.DT_BF16: 1e-2, synth.DT_F16: 1e-2}
 TOL_ABS = 1e-6
 
 
@@ -29,7 +29,7 @@ class HipRun:
 
     def __init__(self, w, ldx=None, ldy=None, ldc=None):
         self.w = w
-        if w.dtype == synth.DT_BF16:
+        if w.dtype != synth.DT_F32:
             self.X = _dev(w.X_bits.view(np.int16), ldx)
             self.Y = _dev(w.Y_bits.view(np.int16), ldy)
         else:

@@ -249,12 +249,13 @@ def test_accumulate_with_split_k_and_padded_c(variant):
 
 
 @pytest.mark.parametrize("variant", range(mm.mmm_matmul_variant_count()))
-def test_bf16_every_variant(variant):
+@pytest.mark.parametrize("dtype", [synth.DT_BF16, synth.DT_F16])
+def test_16_bit_inputs_every_variant(variant, dtype):
     mm.mmm_set_option("matmul_variant", variant)
     mm.mmm_set_option("split_k", 1)
     short = mm.mmm_matmul_variant_name(variant).startswith("R2")
-    w = synth.random_masked(30 if short else 100, 1500, 160, 32, 0.3, 0.4, 300 + variant, dist="smallint", dtype=synth.DT_BF16)
-    check_workload(w, f"bf16 variant {variant}", exact=True)
+    w = synth.random_masked(30 if short else 100, 1500, 160, 32, 0.3, 0.4, 300 + variant, dist="smallint", dtype=dtype)
+    check_workload(w, f"dtype {dtype} variant {variant}", exact=True)
 
 
 def test_autotune_fixes_a_plan_and_keeps_the_result():
@@ -284,11 +285,28 @@ def test_run_to_run_bitwise_reproducible():
     np.testing.assert_array_equal(C3, C4)
 
 
-def test_bf16_small():
-    w = synth.random_masked(32, 520, 96, 16, 0.3, 0.3, 17, dist="normal", dtype=synth.DT_BF16)
-    check_workload(w, "bf16 small")
-    w = synth.random_masked(45, 260, 64, 8, 0.3, 0.3, 18, dist="smallint", dtype=synth.DT_BF16)
-    check_workload(w, "bf16 int", exact=True)
+@pytest.mark.parametrize("dtype", [synth.DT_BF16, synth.DT_F16])
+def test_16_bit_inputs_small(dtype):
+    w = synth.random_masked(32, 520, 96, 16, 0.3, 0.3, 17, dist="normal", dtype=dtype)
+    check_workload(w, f"dtype {dtype} small")
+    w = synth.random_masked(45, 260, 64, 8, 0.3, 0.3, 18, dist="smallint", dtype=dtype)
+    check_workload(w, f"dtype {dtype} int", exact=True)
+
+
+def test_f16_predicates_and_tiny_values():
+    """Half-precision denormals are non-zero and widen exactly; ReLU-style and magnitude predicates act on the value."""
+    rng = np.random.default_rng(5)
+    M, K, N, bw = 40, 200, 64, 16
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    X[0, :6] = np.array([0.0, -0.0, 6e-8, -6e-8, 6.1e-5, -65504.0], dtype=np.float16)
+    Y = rng.standard_normal((K, N)).astype(np.float16)
+    Y[3, 16:32] = 0.0
+    Y[3, 20] = np.float16(6e-8)          # a denormal occupies its block
+    for pred, thr in [(synth.PRED_NONZERO, 0.0), (synth.PRED_GT, 0.0), (synth.PRED_ABS_GT, 0.5)]:
+        w = synth.Workload("f16 pred", M, K, N, bw, synth.DT_F16, X.astype(np.float32), Y.astype(np.float32), pred=pred,
+                           threshold=thr)
+        w.X_bits, w.Y_bits = X.view(np.uint16), Y.view(np.uint16)
+        check_workload(w, f"f16 pred {pred} thr {thr}")
 
 
 def test_random_shapes_sweep():
@@ -302,7 +320,7 @@ def test_random_shapes_sweep():
         if rng.random() < 0.3:
             M = int(rng.integers(1, 33))
         p_a, p_b = (float(rng.choice([0.02, 0.1, 0.3, 0.7, 1.0])) for _ in range(2))
-        dtype = int(rng.choice([synth.DT_F32, synth.DT_BF16]))
+        dtype = int(rng.choice([synth.DT_F32, synth.DT_BF16, synth.DT_F16]))
         variant, split = int(rng.integers(-1, nv)), int(rng.integers(0, 5))
         if variant >= 0 and mm.mmm_matmul_variant_name(variant).startswith("R2") and M > 32:
             variant = -1
