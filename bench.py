@@ -118,6 +118,18 @@ def main():
     wall_ms = (t1 - t0) * 1e3
     ms_per_step = wall_ms / K
 
+    # the paper's protocol beside it: 10 trials of 20 steps each, median and minimum
+    trials = []
+    for _ in range(10):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(20):
+            build()
+            matmul()
+        torch.cuda.synchronize()
+        trials.append((time.perf_counter() - t0) * 1e3 / 20)
+    trials.sort()
+
     # the same K steps once more with an event after every launch (events on the launch stream):
     # per-kernel durations for the roofline.  The events themselves cost several microseconds per
     # step, which is why this pass is not the one that gives the throughput.
@@ -218,6 +230,7 @@ def main():
         "dense_equivalent_gflops": dense_flops / (ms_per_step * 1e-3) / 1e9,
         "t_build_us": t_build * 1e3, "t_matmul_us": t_matmul * 1e3,
         "kernel_timing": "second pass of the same steps with a HIP event after every launch",
+        "trials_10x20": {"median_ms_per_step": 0.5 * (trials[4] + trials[5]), "min_ms_per_step": trials[0]},
         "roofline": roofline,
     }
     if cold_ms is not None:
@@ -272,21 +285,34 @@ def main():
         oracle.mmm(w.X, w.Y, ab, bb, w.bw, want_mag=False, rows=(0, probe))
         t_probe = time.perf_counter() - t
         rows = int(min(w.M, max(probe, 10.0 / max(t_probe / probe, 1e-9))))
-        reps, t_rows = 0, 0.0          # small workloads: repeat the sample until it has run for about 2 s
-        while reps == 0 or (t_rows < 2.0 and reps < 1000):
-            t = time.perf_counter()
-            oracle.mmm(w.X, w.Y, ab, bb, w.bw, want_mag=False, rows=(0, rows))
-            t_rows += time.perf_counter() - t
-            reps += 1
-        t_rows /= reps
+
+        def timed_rows(nrows, budget):   # small workloads: repeat the sample until it has run for about `budget` s
+            reps, total = 0, 0.0
+            while reps == 0 or (total < budget and reps < 1000):
+                t = time.perf_counter()
+                oracle.mmm(w.X, w.Y, ab, bb, w.bw, want_mag=False, rows=(0, nrows))
+                total += time.perf_counter() - t
+                reps += 1
+            return total / reps, reps
+
+        t_rows, reps = timed_rows(rows, 2.0)
         a_rows = synth.unpack_bits(ab[:rows], w.K).sum(axis=0).astype(np.int64)
         b_rows = synth.unpack_bits(bb, NB).sum(axis=1).astype(np.int64)
         macs_sample = int((a_rows * b_rows).sum()) * w.bw
         t_total = t_rows + t_maps * rows / w.M
+        cores = oracle.threads()
         out["cpu_baseline"] = {"value": 2.0 * macs_sample / t_total / 1e9, "unit": "GFLOP/s",
-                               "cores": oracle.threads(), "kind": "oracle",
+                               "cores": cores, "kind": "oracle",
                                "sample": f"rows 0..{rows} of {w.M} (maps in full, pro-rated), {t_total * 1e3:.1f} ms per run, mean of {reps} runs",
                                "ms_per_step_extrapolated": t_total * w.M / rows * 1e3}
+        # the same multiplication on one core (a smaller sample of rows)
+        rows1 = max(1, rows // cores)
+        oracle.set_threads(1)
+        t1, reps1 = timed_rows(rows1, 2.0)
+        oracle.set_threads(cores)
+        a1 = synth.unpack_bits(ab[:rows1], w.K).sum(axis=0).astype(np.int64)
+        out["cpu_baseline"]["one_core"] = {"value": 2.0 * int((a1 * b_rows).sum()) * w.bw / t1 / 1e9, "unit": "GFLOP/s",
+                                           "sample": f"rows 0..{rows1}, multiplication only, mean of {reps1} runs"}
     print(json.dumps(out))
 
 

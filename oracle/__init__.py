@@ -56,6 +56,10 @@ def threads() -> int:
     return int(_L().oracle_threads())
 
 
+def set_threads(n: int) -> None:
+    _L().oracle_set_threads(int(n))
+
+
 def a_bits(X, pred=PRED_NONZERO, threshold=0.0, keep_bits=None) -> np.ndarray:
     X = _f32(X)
     M, K = X.shape

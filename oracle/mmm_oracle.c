@@ -75,6 +75,16 @@ int oracle_threads(void)
 #endif
 }
 
+/* How many threads the row loops may use from now on (timing on one core and on all). */
+void oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /* M evaluated element by element (sections 1, 3: masks evaluated at run time;
  * zero test as in Fig. "skip computation when A is sparse").
  * a_bits: M x ceil(K/64) words, cleared here. */
