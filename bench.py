@@ -55,7 +55,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards without communication, "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "by rows or by block columns of C); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
