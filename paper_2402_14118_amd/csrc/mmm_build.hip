@@ -102,7 +102,8 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
             if (r < p.M && k < p.K) u[j][h] = f32_bits<T>(X[r * p.ldx + k]);
         }
     }
-    uint64_t colany[A_WORDS] = {0, 0}, mine = 0;
+    uint64_t colany[A_WORDS] = {0, 0};
+    uint32_t mine_lo = 0, mine_hi = 0;   // lane 2j+h: the bitmap word of (row j, half h)
 #pragma unroll
     for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
 #pragma unroll
@@ -111,9 +112,12 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
             m &= ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(kw >> 32), 2 * j + h) << 32) |
                  (uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)kw, 2 * j + h);
             colany[h] |= m;
-            if (lane == 2 * j + h) mine = m;
+            const bool owner = __builtin_amdgcn_inverse_ballot_w64(1ull << (2 * j + h));   // lane 2j+h, as a constant mask
+            mine_lo = owner ? (uint32_t)m : mine_lo;
+            mine_hi = owner ? (uint32_t)(m >> 32) : mine_hi;
         }
     }
+    const uint64_t mine = ((uint64_t)mine_hi << 32) | mine_lo;
     // bitmap words and per-wave entry offsets
     const bool have_word = lane < 2 * A_ROWS_PER_WAVE && rbase + (lane >> 1) < p.M && w_lo + (lane & 1) < p.WA;
     if (have_word) p.a_bits[(rbase + (lane >> 1)) * p.WA + w_lo + (lane & 1)] = mine;
@@ -152,12 +156,12 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
     for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
 #pragma unroll
         for (int h = 0; h < A_WORDS; ++h) {
-            const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)mine, 2 * j + h);
-            const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(mine >> 32), 2 * j + h);
+            const uint32_t lo = __builtin_amdgcn_readlane(mine_lo, 2 * j + h);
+            const uint32_t hi = __builtin_amdgcn_readlane(mine_hi, 2 * j + h);
             const uint64_t m = ((uint64_t)hi << 32) | lo;
             if (m == 0) continue;
             const uint32_t off = base + __builtin_amdgcn_readlane(excl, 2 * j + h);
-            if ((m >> lane) & 1ull) {
+            if (__builtin_amdgcn_inverse_ballot_w64(m)) {   // the word is the lane mask of its own non-zero elements
                 const uint32_t slab = mmm_slab_pos((uint32_t)(wave * A_ROWS_PER_WAVE + j), (uint32_t)(64 * h + lane));
                 ent[off + mbcnt64(m)] = make_uint2(slab, u[j][h]);
             }
