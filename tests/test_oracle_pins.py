@@ -275,6 +275,32 @@ def test_generators_are_seeded_and_shaped():
     np.testing.assert_array_equal(v, np.array([1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7], dtype=np.float32))
 
 
+def test_half_inputs_and_column_structured_generator():
+    # IEEE half rounding is numpy's; the bit patterns and the widened values describe the same numbers
+    w = synth.random_masked(24, 80, 48, 16, 0.4, 0.5, 9, dist="normal", dtype=synth.DT_F16)
+    np.testing.assert_array_equal(w.X_bits.view(np.float16).astype(np.float32), w.X)
+    np.testing.assert_array_equal(w.Y_bits.view(np.float16).astype(np.float32), w.Y)
+    assert np.all(np.abs(w.X) < 65504)
+    ab, bb, C, mag = oracle.run_workload(w)
+    a_nz, b_occ = np_masks(w)
+    np.testing.assert_array_equal(ab, synth.pack_bits(a_nz))
+    ref, _ = np_product64(w)
+    assert np.all(np.abs(C - ref) <= np.abs(ref) * 2.0 ** -23 + 1e-30)
+    # column-structured A: the columns of A that are on and the rows of B that are on come from one set
+    w = synth.column_sparse(40, 300, 96, 16, 0.2, 0.6, 0.7, 4)
+    ab, bb, C, mag = oracle.run_workload(w)
+    sel = synth.unpack_bits(w.keep_rows.reshape(1, -1), w.K)[0]
+    assert 0.1 < sel.mean() < 0.3
+    assert not (synth.unpack_bits(ab, w.K).any(axis=0) & ~sel).any()
+    assert not (synth.unpack_bits(bb, w.N // w.bw).any(axis=1) & ~sel).any()
+    ref, _ = np_product64(w)
+    assert np.all(np.abs(C - ref) <= np.abs(ref) * 2.0 ** -23 + 1e-30)
+    # only the selected k contribute: the product over the selected columns alone is the same
+    A = np.where(synth.unpack_bits(ab, w.K), w.X, 0).astype(np.float64)
+    B = np.where(np.repeat(synth.unpack_bits(bb, w.N // w.bw), w.bw, axis=1), w.Y, 0).astype(np.float64)
+    np.testing.assert_allclose(A[:, sel] @ B[sel, :], ref, rtol=1e-12, atol=1e-12)
+
+
 @pytest.mark.parametrize("n", [1, 2, 3, 4, 5])
 def test_scaled_configs_run_and_agree_with_numpy(n):
     w = synth.config(n, scale=16)
