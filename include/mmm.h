@@ -14,11 +14,14 @@
  *
  * Conventions for every call
  *   - Pointers named X, Y, C, keep_*, dev_workspace are DEVICE pointers owned by
- *     the caller.  The library never allocates or frees device memory and keeps
- *     no pointer to X, Y or C after a call returns.
+ *     the caller.  The library never allocates or frees device memory and never
+ *     reads X, Y or C after the work of a call has run; the handle remembers the
+ *     address and leading dimension of the X its A side was built from, only to
+ *     compare them with what mmm_matmul is given.
  *   - Row-major; leading dimensions (ldx, ldy, ldc) are in elements and must be
  *     >= the row length; ldx and ldy must be below 2^22 (MMM_ERR_SHAPE
- *     otherwise).  C is always float.
+ *     otherwise, from mmm_build_maps and from mmm_matmul alike).  C is always
+ *     float.
  *   - Bitmaps: LSB-first little-endian 64-bit words, row-major, every row padded
  *     to whole words, pad bits zero: bit (c mod 64) of word (c div 64) of row r
  *     describes column c of row r.  (The paper prints patterns first-vector-
@@ -28,8 +31,14 @@
  *   - Errors are return codes.  Arguments are checked on the host before any
  *     device work is enqueued; on error nothing is launched and no output is
  *     touched.  No call aborts or prints.
- *   - Inputs are assumed finite inside kept B blocks.  Masked-out elements of X
- *     and blocks of Y never reach the arithmetic, whatever they hold.
+ *   - Masked-out elements of X and switched-off blocks of Y never reach the
+ *     arithmetic, whatever they hold.  Values inside occupied blocks of Y are
+ *     expected to be finite.  If Y[k,j] inside an occupied block is Inf or NaN,
+ *     column j of C is affected and no other column: C[i,j] is non-finite for
+ *     every row i whose a_bits[i,k] is set (as the definition gives), and for the
+ *     remaining rows it is either the value of the definition or NaN (the matrix
+ *     instruction path multiplies an occupied block by explicit zeros for rows
+ *     whose element of A is zero).
  */
 #ifndef MMM_H
 #define MMM_H
@@ -167,14 +176,18 @@ mmm_status mmm_maps_stats(const mmm_maps *maps, uint64_t *nnz_a, uint64_t *occup
  *     C[i,j] (+)= sum over k with a_bits[i,k] & b_bits[k, j div bw] of X[i,k] * Y[k,j]
  * (paper, section 3 "Matrix Multiplication", Fig. "MMM Pseudocode").  X and Y
  * must hold the same values the maps were built from: the values of A are taken
- * from the lists mmm_build_maps wrote (X is checked like any argument but not
- * read again), those of B from Y.  Products the maps skip contribute exactly 0,
- * whatever the skipped operands hold; kept operands are assumed finite.  Every
- * element of C is written exactly once, zeros included.  float accumulation; the result is
- * bitwise reproducible from run to run for the same inputs and shape.
+ * from the lists mmm_build_maps wrote (X is not read again), those of B from Y.
+ * WARNING: after X has been changed in place the A side must be rebuilt
+ * (mmm_build_maps with Y == NULL) before the next mmm_matmul; otherwise C is
+ * computed from the old values without any error.  What can be checked is: X
+ * and ldx must be the ones the A side was built from (MMM_ERR_MAPS_MISMATCH).
+ * Products the maps skip contribute exactly 0, whatever the skipped operands
+ * hold (see the conventions above for non-finite kept values).  Every element
+ * of C is written exactly once, zeros included.  float accumulation; the
+ * result is bitwise reproducible from run to run for the same inputs and shape.
  * Errors: MMM_ERR_INVALID_ARG, MMM_ERR_SHAPE, MMM_ERR_DTYPE,
- * MMM_ERR_MAPS_MISMATCH (a side not built, or dt differs from the build),
- * MMM_ERR_DEVICE. */
+ * MMM_ERR_MAPS_MISMATCH (a side not built, dt differs from the build, or X / ldx
+ * are not those of the build), MMM_ERR_DEVICE. */
 mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt,
                       const void *X, int64_t ldx, const void *Y, int64_t ldy,
                       float *C, int64_t ldc, int32_t accumulate, void *hip_stream);

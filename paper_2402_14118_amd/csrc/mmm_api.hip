@@ -179,6 +179,8 @@ mmm_status mmm_maps_init(void *dev_workspace, size_t workspace_bytes, int64_t M,
     m->ws_bytes = workspace_bytes;
     m->a_built = m->b_built = false;
     m->a_dtype = m->b_dtype = -1;
+    m->a_src = nullptr;
+    m->a_src_ld = 0;
     m->plan_variant = -1;
     m->plan_split = 0;
     *out = m;
@@ -198,7 +200,7 @@ mmm_status mmm_build_maps(mmm_maps *maps, mmm_dtype dt, const void *X, int64_t l
     if (X != nullptr) {
         if (ma == nullptr) return MMM_ERR_INVALID_ARG;
         if (ma->pred < MMM_PRED_NONZERO || ma->pred > MMM_PRED_ABS_GT) return MMM_ERR_INVALID_ARG;
-        if (ldx < maps->K) return MMM_ERR_SHAPE;
+        if (ldx < maps->K || ldx > kMaxLd) return MMM_ERR_SHAPE;
         if (reinterpret_cast<uintptr_t>(X) % esz != 0) return MMM_ERR_DTYPE;
         if (ma->keep_bits != nullptr && reinterpret_cast<uintptr_t>(ma->keep_bits) % 8 != 0) return MMM_ERR_INVALID_ARG;
         a.X = X;
@@ -210,7 +212,7 @@ mmm_status mmm_build_maps(mmm_maps *maps, mmm_dtype dt, const void *X, int64_t l
     if (Y != nullptr) {
         if (mb == nullptr) return MMM_ERR_INVALID_ARG;
         if (mb->block_width != maps->bw) return MMM_ERR_SHAPE;
-        if (ldy < maps->N) return MMM_ERR_SHAPE;
+        if (ldy < maps->N || ldy > kMaxLd) return MMM_ERR_SHAPE;
         if (reinterpret_cast<uintptr_t>(Y) % esz != 0) return MMM_ERR_DTYPE;
         if ((mb->keep_rows != nullptr && reinterpret_cast<uintptr_t>(mb->keep_rows) % 8 != 0) ||
             (mb->keep_blocks != nullptr && reinterpret_cast<uintptr_t>(mb->keep_blocks) % 8 != 0))
@@ -227,6 +229,8 @@ mmm_status mmm_build_maps(mmm_maps *maps, mmm_dtype dt, const void *X, int64_t l
     if (X != nullptr) {
         maps->a_built = true;
         maps->a_dtype = dt;
+        maps->a_src = X;   // compared, never dereferenced
+        maps->a_src_ld = ldx;
     }
     if (Y != nullptr) {
         maps->b_built = true;
@@ -312,6 +316,8 @@ mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t
         return MMM_ERR_DTYPE;
     if (!maps->a_built || !maps->b_built) return MMM_ERR_MAPS_MISMATCH;
     if (maps->a_dtype != dt || maps->b_dtype != dt) return MMM_ERR_MAPS_MISMATCH;
+    // the values of A travel in the lists that were copied from X at build time: another X is another A
+    if (maps->a_src != X || maps->a_src_ld != ldx) return MMM_ERR_MAPS_MISMATCH;
     const mmm_plan p = make_plan(maps, dt);
     if (hipError_t e = mmm_launch_matmul(maps, p, dt, X, ldx, Y, ldy, C, ldc, accumulate ? 1 : 0,
                                          static_cast<hipStream_t>(hip_stream));

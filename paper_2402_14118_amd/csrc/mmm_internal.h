@@ -53,6 +53,8 @@ struct mmm_maps {
     // state
     bool a_built, b_built;
     int32_t a_dtype, b_dtype;
+    const void *a_src;   // address and leading dimension of the X the A side was built from (identity only)
+    int64_t a_src_ld;
     // launch plan fixed for this handle (-1 / 0: none, follow the process-wide options)
     int32_t plan_variant, plan_split;
 };

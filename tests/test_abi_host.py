@@ -65,6 +65,13 @@ def test_init_and_call_validation_without_device():
         assert L.mmm_build_maps(maps, 0, X, 127, r(ma), Y, 64, r(mb), None) == B.MMM_ERR_SHAPE
         assert L.mmm_build_maps(maps, 0, X, 128, r(ma), Y, 63, r(mb), None) == B.MMM_ERR_SHAPE
         assert L.mmm_build_maps(maps, 0, X + 2, 128, r(ma), Y, 64, r(mb), None) == B.MMM_ERR_DTYPE
+        # leading dimensions of 2^22 elements and more are refused by the builder and by the multiplication alike
+        big = 1 << 22
+        assert L.mmm_build_maps(maps, 0, X, big, r(ma), Y, 64, r(mb), None) == B.MMM_ERR_SHAPE
+        assert L.mmm_build_maps(maps, 0, X, 128, r(ma), Y, big, r(mb), None) == B.MMM_ERR_SHAPE
+        assert L.mmm_build_maps(maps, 0, None, 0, None, Y, big, r(mb), None) == B.MMM_ERR_SHAPE
+        assert L.mmm_matmul(maps, 0, X, big, Y, 64, C, 64, 0, None) == B.MMM_ERR_SHAPE
+        assert L.mmm_matmul(maps, 0, X, 128, Y, big, C, 64, 0, None) == B.MMM_ERR_SHAPE
         assert L.mmm_build_maps(maps, 0, X, 128, r(mm.MaskA(3, 0.0, None)), Y, 64, r(mb), None) == B.MMM_ERR_INVALID_ARG
         assert L.mmm_build_maps(maps, 0, X, 128, r(ma), Y, 64, r(mm.MaskB(8, None, None)), None) == B.MMM_ERR_SHAPE
         # nothing built yet: the multiplication and the statistics refuse

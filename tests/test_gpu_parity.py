@@ -168,18 +168,61 @@ def test_predicates_and_special_values():
     np.testing.assert_array_equal(run.maps_host()[0], ab)
 
 
-def test_masked_positions_may_hold_anything():
-    """Masked-out X elements and switched-off Y blocks never reach the arithmetic."""
-    w = synth.random_masked(64, 256, 128, 16, 0.3, 0.3, 5, dist="smallint")
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16, synth.DT_F16])
+@pytest.mark.parametrize("bw,N", [(8, 136), (16, 128), (32, 160)])
+def test_masked_positions_may_hold_anything(bw, N, dtype):
+    """Masked-out X elements and switched-off Y blocks never reach the arithmetic.  With bw = 8 a 16-column group of
+    the multiplier spans two blocks (and N = 136 leaves half a group at the edge), with bw = 32 a block spans two
+    groups."""
+    w = synth.random_masked(64, 256, N, bw, 0.3, 0.3, 5 + bw, dist="smallint", dtype=dtype)
     ab, bb, C_ref, _ = oracle.run_workload(w)
     keepa = synth.unpack_bits(w.keep_a, w.K)
     keepb = np.repeat(synth.unpack_bits(w.keep_blocks, w.N // w.bw), w.bw, axis=1)
     w.X = np.where(keepa, w.X, np.float32(np.nan))
     w.Y = np.where(keepb, w.Y, np.float32(np.inf))
+    if dtype == synth.DT_BF16:
+        w.X_bits, w.Y_bits = synth.round_to_bf16(w.X)[0], synth.round_to_bf16(w.Y)[0]
+    elif dtype == synth.DT_F16:
+        w.X_bits, w.Y_bits = synth.round_to_f16(w.X)[0], synth.round_to_f16(w.Y)[0]
     a_hip, b_hip, C = HipRun(w).run()
     np.testing.assert_array_equal(a_hip, ab)
     np.testing.assert_array_equal(b_hip, bb)
     np.testing.assert_array_equal(C, C_ref)
+
+
+@pytest.mark.parametrize("bw", [8, 16, 32])
+def test_non_finite_value_inside_an_occupied_block(bw):
+    """The stated contract for a kept Inf in Y: only its column of C is affected; rows whose element of A at that k is
+    non-zero get a non-finite result, the other rows of that column the exact value or NaN."""
+    w = synth.random_masked(100, 300, 160, bw, 0.3, 0.5, 41 + bw, dist="smallint")
+    bb0 = oracle.b_bits(w.Y, bw, w.keep_rows, w.keep_blocks)
+    k, jb = [int(v[0]) for v in np.nonzero(synth.unpack_bits(bb0, w.N // bw))]      # some occupied block
+    j = jb * bw + 3
+    w.Y[k, j] = np.inf
+    ab, bb, C_ref, _ = oracle.run_workload(w)
+    np.testing.assert_array_equal(bb, bb0)
+    a_hip, b_hip, C = HipRun(w).run()
+    np.testing.assert_array_equal(a_hip, ab)
+    np.testing.assert_array_equal(b_hip, bb)
+    other = np.arange(w.N) != j
+    np.testing.assert_array_equal(C[:, other], C_ref[:, other])
+    hit = synth.unpack_bits(ab, w.K)[:, k]
+    assert hit.any() and not hit.all()
+    assert not np.isfinite(C_ref[hit, j]).any() and np.isfinite(C_ref[~hit, j]).all()     # what the definition gives
+    assert not np.isfinite(C[hit, j]).any()
+    rest = C[~hit, j]
+    assert np.all(np.isnan(rest) | (rest == C_ref[~hit, j]))
+
+
+def test_matmul_refuses_another_x_than_the_one_built_from():
+    w = synth.random_masked(40, 100, 64, 16, 0.3, 0.3, 77, dist="smallint")
+    run = HipRun(w)
+    run.build()
+    X2 = run.X.clone()
+    with pytest.raises(mm.MmmError) as e:
+        run.eng.matmul(X2, run.Y, run.C)
+    assert e.value.status == mm.binding.MMM_ERR_MAPS_MISMATCH
+    run.matmul()          # the X it was built from is accepted
 
 
 def test_identity_zero_and_full_masks():
@@ -354,34 +397,14 @@ def test_config5_full_bf16_decode():
     print("plan", run.eng.plan())
 
 
-def sampled_check(w, what, n_rows=48, n_elems=64):
-    """Full-size run in the benchmark's launch configuration, compared on sampled
-    rows (whole rows from the oracle) and sampled single elements."""
-    print(f"case {what}: M={w.M} K={w.K} N={w.N} bw={w.bw}", flush=True)
-    ab = oracle.a_bits(w.X, w.pred, w.threshold, w.keep_a)
-    bb = oracle.b_bits(w.Y, w.bw, w.keep_rows, w.keep_blocks)
-    run = HipRun(w)
-    a_hip, b_hip, C = run.run()
-    np.testing.assert_array_equal(a_hip, ab, err_msg=what)
-    np.testing.assert_array_equal(b_hip, bb, err_msg=what)
-    assert run.eng.stats() == oracle.counts(ab, bb, w.M, w.K, w.N, w.bw)
-    rng = np.random.default_rng(99)
-    rows = np.unique(np.concatenate([[0, w.M - 1], rng.integers(0, w.M, n_rows)]))
-    for r in rows:
-        Cr, mag = oracle.mmm(w.X, w.Y, ab, bb, w.bw, rows=(int(r), int(r) + 1))
-        assert_close(C[r:r + 1], Cr[r:r + 1], mag[r:r + 1], w.dtype, f"{what} row {r}")
-    for _ in range(n_elems):
-        i, j = int(rng.integers(0, w.M)), int(rng.integers(0, w.N))
-        c, m = oracle.mmm_element(w.X, w.Y, ab, bb, w.bw, i, j)
-        assert abs(float(C[i, j]) - c) <= 1e-5 * m + 1e-6, (what, i, j)
-    assert np.isfinite(C).all()
+@pytest.mark.parametrize("ip", range(len(synth.SWEEP_P)))
+def test_config3_full(ip):
+    """Every point of the sparsity sweep at full size, in the launch configuration the benchmark times, element by
+    element against the oracle."""
+    run, _ = check_workload(synth.config(3, ip), f"config 3 p={synth.SWEEP_P[ip]}")
     print("plan", run.eng.plan(), flush=True)
 
 
-@pytest.mark.parametrize("ip", [0, 3, 4])
-def test_config3_full_sampled(ip):
-    sampled_check(synth.config(3, ip), f"config 3 p={synth.SWEEP_P[ip]}")
-
-
-def test_config4_full_sampled():
-    sampled_check(synth.config(4), "config 4", n_rows=24)
+def test_config4_full():
+    run, _ = check_workload(synth.config(4), "config 4")
+    print("plan", run.eng.plan(), flush=True)

@@ -147,6 +147,31 @@ def test_zero_masks_give_plus_zero():
     assert oracle.counts(ab, bb, w.M, w.K, w.N, w.bw)[2] == 0
 
 
+def test_skipped_operands_never_reach_the_sum_and_kept_infinity_follows_the_definition():
+    """Skipping semantics pinned by a pure-Python loop that really skips (not by a dense product, where 0 x Inf would
+    be NaN): junk at masked positions changes nothing, and an Inf inside an occupied block reaches exactly the rows
+    whose element of A at that k is non-zero."""
+    w = tiny(9, 24, 16, 4, 0.4, 0.5, 12, dist="smallint")
+    a_nz, b_occ = np_masks(w)
+    k, jb = [int(v[0]) for v in np.nonzero(b_occ)]
+    j = jb * w.bw + 1
+    w.Y[k, j] = np.inf
+    w.X = np.where(synth.unpack_bits(w.keep_a, w.K), w.X, np.float32(np.nan))
+    w.Y = np.where(np.repeat(synth.unpack_bits(w.keep_blocks, w.N // w.bw), w.bw, axis=1), w.Y, np.float32(-np.inf))
+    want = np.zeros((w.M, w.N))
+    for i in range(w.M):
+        for jj in range(w.N):
+            for kk in range(w.K):
+                if a_nz[i, kk] and b_occ[kk, jj // w.bw]:
+                    want[i, jj] += float(w.X[i, kk]) * float(w.Y[kk, jj])
+    ab, bb, C, _ = oracle.run_workload(w)
+    np.testing.assert_array_equal(synth.unpack_bits(ab, w.K), a_nz)
+    np.testing.assert_array_equal(synth.unpack_bits(bb, w.N // w.bw), b_occ)
+    np.testing.assert_array_equal(C, want.astype(np.float32))
+    assert np.isinf(C[a_nz[:, k], j]).all() and np.isfinite(C[~a_nz[:, k], j]).all() and a_nz[:, k].any()
+    assert np.isfinite(np.delete(C, j, axis=1)).all()
+
+
 def test_accumulate_mode():
     w = tiny(10, 64, 32, 16, 0.5, 0.5, 9, dist="smallint")
     ab, bb, C, _ = oracle.run_workload(w)
