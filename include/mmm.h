@@ -192,6 +192,28 @@ mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt,
                       const void *X, int64_t ldx, const void *Y, int64_t ldy,
                       float *C, int64_t ldc, int32_t accumulate, void *hip_stream);
 
+/* The same multiplication for callers that cannot allocate and must not have
+ * memory allocated on their behalf while they run: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  mmm_matmul keeps the
+ * partial sums of a K-split multiplication (few tiles of C, long K: the decode
+ * shape) in the caller's workspace; this entry point keeps them in an array that
+ * is part of the library's own device image instead (MMM_STATIC_SCRATCH_BYTES
+ * bytes on every GPU the library runs on, held until the process ends), so the
+ * call touches no allocator at all.  Same arguments, same launch plan, same
+ * kernels and bit-identical results as mmm_matmul.
+ * Limit: split_k * M * N * 4 bytes of partial sums must fit the array, else
+ * MMM_ERR_WORKSPACE (mmm_last_device_error() then says how many bytes were
+ * needed); a plan that does not split K needs no scratch and is always accepted.
+ * The partial sums are fully overwritten before they are read, so nothing is
+ * cleared between calls.  All calls on one GPU share that GPU's array: two calls
+ * that may run at the same time on one GPU (different streams) race; calls on
+ * one stream do not.
+ * Errors: as mmm_matmul, plus MMM_ERR_WORKSPACE as described. */
+#define MMM_STATIC_SCRATCH_BYTES (16u << 20)
+mmm_status mmm_matmul_static_scratch(const mmm_maps *maps, mmm_dtype dt,
+                                     const void *X, int64_t ldx, const void *Y, int64_t ldy,
+                                     float *C, int64_t ldc, int32_t accumulate, void *hip_stream);
+
 /* Process-wide tuning knobs (for benchmarking; the defaults choose by shape).
  *   "matmul_variant": -1 = automatic, else index of a compiled tile variant
  *   "split_k"       :  0 = automatic, else the number of K splits to use

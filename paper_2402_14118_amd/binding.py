@@ -26,7 +26,7 @@ MMM_PRED_NONZERO, MMM_PRED_GT, MMM_PRED_ABS_GT = 0, 1, 2
 
 EXPORTS = [
     "mmm_maps_workspace_bytes", "mmm_maps_init", "mmm_maps_release", "mmm_build_maps", "mmm_maps_view",
-    "mmm_maps_view_derived", "mmm_maps_view_lists", "mmm_maps_stats", "mmm_matmul", "mmm_set_option", "mmm_matmul_variant_count",
+    "mmm_maps_view_derived", "mmm_maps_view_lists", "mmm_maps_stats", "mmm_matmul", "mmm_matmul_static_scratch", "mmm_set_option", "mmm_matmul_variant_count",
     "mmm_matmul_variant_name", "mmm_matmul_plan", "mmm_maps_set_plan", "mmm_status_string", "mmm_last_device_error",
 ]
 
@@ -42,7 +42,9 @@ class MaskB(ctypes.Structure):
 class MmmError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        detail = f" [{mmm_last_device_error()}]" if status == MMM_ERR_DEVICE else ""
+        detail = ""
+        if status == MMM_ERR_DEVICE or (status == MMM_ERR_WORKSPACE and where == "mmm_matmul_static_scratch"):
+            detail = f" [{mmm_last_device_error()}]"
         super().__init__(f"{where}: {status_string(status)} (status {status}){detail}")
 
 
@@ -64,6 +66,7 @@ def _load() -> ctypes.CDLL:
     lib.mmm_maps_view_lists.argtypes = [vp, c.POINTER(vp), c.POINTER(vp), c.POINTER(i64), c.POINTER(i64), c.POINTER(i64)]
     lib.mmm_maps_stats.argtypes = [vp, c.POINTER(c.c_uint64), c.POINTER(c.c_uint64), c.POINTER(c.c_uint64), vp]
     lib.mmm_matmul.argtypes = [vp, i32, vp, i64, vp, i64, vp, i64, i32, vp]
+    lib.mmm_matmul_static_scratch.argtypes = [vp, i32, vp, i64, vp, i64, vp, i64, i32, vp]
     lib.mmm_set_option.argtypes = [c.c_char_p, i64]
     lib.mmm_maps_set_plan.argtypes = [vp, i32, i32]
     lib.mmm_matmul_variant_count.restype = i32
@@ -170,6 +173,12 @@ def mmm_maps_stats(maps: int, stream=None):
 def mmm_matmul(maps: int, dt: int, X, ldx: int, Y, ldy: int, C, ldc: int, accumulate: int = 0, stream=None) -> None:
     _check(lib.mmm_matmul(maps, dt, _ptr(X), ldx, _ptr(Y), ldy, _ptr(C), ldc, int(accumulate), _stream(stream)),
            "mmm_matmul")
+
+
+def mmm_matmul_static_scratch(maps: int, dt: int, X, ldx: int, Y, ldy: int, C, ldc: int, accumulate: int = 0,
+                              stream=None) -> None:
+    _check(lib.mmm_matmul_static_scratch(maps, dt, _ptr(X), ldx, _ptr(Y), ldy, _ptr(C), ldc, int(accumulate),
+                                         _stream(stream)), "mmm_matmul_static_scratch")
 
 
 def mmm_maps_set_plan(maps: int, variant: int = -1, split_k: int = 0) -> None:

@@ -303,8 +303,10 @@ mmm_status mmm_matmul_plan(const mmm_maps *maps, mmm_dtype dt, int32_t *variant,
     return MMM_OK;
 }
 
-mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const void *Y, int64_t ldy,
-                      float *C, int64_t ldc, int32_t accumulate, void *hip_stream)
+}   // extern "C"
+
+static mmm_status matmul_common(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const void *Y, int64_t ldy,
+                                float *C, int64_t ldc, int32_t accumulate, void *hip_stream, bool static_scratch)
 {
     if (maps == nullptr || X == nullptr || Y == nullptr || C == nullptr) return MMM_ERR_INVALID_ARG;
     if (!dtype_ok(dt)) return MMM_ERR_DTYPE;
@@ -319,13 +321,43 @@ mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t
     // the values of A travel in the lists that were copied from X at build time: another X is another A
     if (maps->a_src != X || maps->a_src_ld != ldx) return MMM_ERR_MAPS_MISMATCH;
     const mmm_plan p = make_plan(maps, dt);
-    if (hipError_t e = mmm_launch_matmul(maps, p, dt, X, ldx, Y, ldy, C, ldc, accumulate ? 1 : 0,
-                                         static_cast<hipStream_t>(hip_stream));
+    float *partials = maps->partials;
+    size_t partial_bytes = maps->partial_bytes;
+    if (static_scratch) {
+        const size_t need = p.split_k > 1 ? (size_t)p.split_k * (size_t)maps->M * (size_t)maps->N * sizeof(float) : 0;
+        if (need > (size_t)MMM_STATIC_SCRATCH_BYTES) {
+            std::snprintf(g_detail, sizeof(g_detail),
+                          "mmm_matmul_static_scratch: %d partial sums of C need %zu bytes, the static scratch holds %zu",
+                          (int)p.split_k, need, (size_t)MMM_STATIC_SCRATCH_BYTES);
+            return MMM_ERR_WORKSPACE;
+        }
+        if (hipError_t e = mmm_static_scratch(&partials); e != hipSuccess) {
+            note_device_error("address of the static scratch", e);
+            return MMM_ERR_DEVICE;
+        }
+        partial_bytes = (size_t)MMM_STATIC_SCRATCH_BYTES;
+    }
+    if (hipError_t e = mmm_launch_matmul(maps, p, dt, X, ldx, Y, ldy, C, ldc, accumulate ? 1 : 0, partials,
+                                         partial_bytes, static_cast<hipStream_t>(hip_stream));
         e != hipSuccess) {
         note_device_error("masked GEMM launch", e);
         return MMM_ERR_DEVICE;
     }
     return MMM_OK;
+}
+
+extern "C" {
+
+mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const void *Y, int64_t ldy,
+                      float *C, int64_t ldc, int32_t accumulate, void *hip_stream)
+{
+    return matmul_common(maps, dt, X, ldx, Y, ldy, C, ldc, accumulate, hip_stream, false);
+}
+
+mmm_status mmm_matmul_static_scratch(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const void *Y,
+                                     int64_t ldy, float *C, int64_t ldc, int32_t accumulate, void *hip_stream)
+{
+    return matmul_common(maps, dt, X, ldx, Y, ldy, C, ldc, accumulate, hip_stream, true);
 }
 
 mmm_status mmm_maps_set_plan(mmm_maps *maps, int32_t variant, int32_t split_k)

@@ -92,6 +92,9 @@ hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStrea
 hipError_t mmm_launch_stats(const mmm_maps *m, hipStream_t s);
 int32_t mmm_variant_count();
 const mmm_variant_info &mmm_variant(int32_t i);
+// partials / partial_bytes: where the split-K partial sums go (used only when p.split_k > 1)
 hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &p, int32_t dtype, const void *X, int64_t ldx,
-                             const void *Y, int64_t ldy, float *C, int64_t ldc, int32_t accumulate,
-                             hipStream_t s);
+                             const void *Y, int64_t ldy, float *C, int64_t ldc, int32_t accumulate, float *partials,
+                             size_t partial_bytes, hipStream_t s);
+// device address of the library's own scratch array on the current device (MMM_STATIC_SCRATCH_BYTES bytes)
+hipError_t mmm_static_scratch(float **ptr);

@@ -33,6 +33,8 @@
 // need few instructions per MFMA, and the workgroup shapes that do best are
 // those that put sixteen waves on a compute unit (eight or sixteen waves per
 // workgroup, one 16-column group per wave).
+#include <mutex>
+
 #include "mmm_internal.h"
 
 namespace {
@@ -547,11 +549,39 @@ constexpr int32_t kVariants = (int32_t)(sizeof(g_variants) / sizeof(g_variants[0
 
 }   // namespace
 
+// Partial sums of the split-K multiplication for callers that cannot bring (or let the library
+// carve out of a workspace) a buffer of their own: one array per GPU, held until the process
+// ends.  Host code never uses the array's name as an address: the device address is looked up
+// once per device and that pointer is what kernels and copies get.
+static __device__ __align__(256) unsigned char scratch[MMM_STATIC_SCRATCH_BYTES];
+
+hipError_t mmm_static_scratch(float **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *addr[kMaxDevices];   // zero-initialised: not looked up yet
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (addr[dev] == nullptr) {   // the current device's own copy of the array
+        void *q = nullptr;
+        e = hipGetSymbolAddress(&q, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (q == nullptr) return hipErrorInvalidSymbol;
+        addr[dev] = q;
+    }
+    *ptr = static_cast<float *>(addr[dev]);
+    return hipSuccess;
+}
+
 int32_t mmm_variant_count() { return kVariants; }
 const mmm_variant_info &mmm_variant(int32_t i) { return g_variants[i].info; }
 
 hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtype, const void *X, int64_t ldx,
-                             const void *Y, int64_t ldy, float *C, int64_t ldc, int32_t accumulate, hipStream_t s)
+                             const void *Y, int64_t ldy, float *C, int64_t ldc, int32_t accumulate, float *partials,
+                             size_t partial_bytes, hipStream_t s)
 {
     (void)X;   // the non-zero values of A travel inside the map (they were copied from X when it was built)
     (void)ldx;
@@ -563,7 +593,7 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtyp
     p.ldy = ldy;
     p.C = C;
     p.ldc = ldc;
-    p.P = m->partials;
+    p.P = partials;
     p.a_cnt = m->a_cnt;
     p.a_ent = reinterpret_cast<const uint2 *>(m->a_ent);
     p.a_colany = m->a_colany;
@@ -585,7 +615,7 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtyp
     p.chunks_per_split = pl.chunks_per_split;
     p.accumulate = accumulate;
     if (pl.workgroups <= 0 || pl.workgroups > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (pl.split_k > 1 && (size_t)pl.split_k * (size_t)m->M * (size_t)m->N * sizeof(float) > m->partial_bytes)
+    if (pl.split_k > 1 && (size_t)pl.split_k * (size_t)m->M * (size_t)m->N * sizeof(float) > partial_bytes)
         return hipErrorInvalidValue;
     const int64_t gw = v.info.groups / (v.info.threads / 64);
     int64_t window = list_words(v.info.threads / 64) / (gw * WPC);   // one map word per lane
@@ -602,7 +632,7 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtyp
         const int64_t total = m->M * m->N;
         int64_t blocks = (total + 255) / 256;
         if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL(mmm_splitk_reduce_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, m->partials, C, ldc,
+        hipLaunchKernelGGL(mmm_splitk_reduce_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, partials, C, ldc,
                            m->M, m->N, pl.split_k, accumulate);
         e = hipGetLastError();
     }

@@ -49,6 +49,11 @@ class MaskedMatmul:
     def matmul(self, X: torch.Tensor, Y: torch.Tensor, C: torch.Tensor, accumulate: bool = False, stream=None) -> None:
         B.mmm_matmul(self.maps, self.dtype, X, X.stride(0), Y, Y.stride(0), C, C.stride(0), int(accumulate), stream)
 
+    def matmul_static_scratch(self, X: torch.Tensor, Y: torch.Tensor, C: torch.Tensor, accumulate: bool = False,
+                              stream=None) -> None:
+        B.mmm_matmul_static_scratch(self.maps, self.dtype, X, X.stride(0), Y, Y.stride(0), C, C.stride(0),
+                                    int(accumulate), stream)
+
     def stats(self, stream=None):
         return B.mmm_maps_stats(self.maps, stream)
 
