@@ -192,6 +192,48 @@ mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt,
                       const void *X, int64_t ldx, const void *Y, int64_t ldy,
                       float *C, int64_t ldc, int32_t accumulate, void *hip_stream);
 
+/* Which kernel mmm_matmul uses.
+ *   MMM_PATH_MATRIX: matrix instructions over the compacted k lists of each 16-column group; skips
+ *       B's empty blocks exactly and A's zeros only where a whole column of a 64-row tile is zero.
+ *       Work grows with B's density alone.
+ *   MMM_PATH_PAIRS : vector FMAs over exactly the products that survive both maps (the loop of
+ *       Fig. "MMM Pseudocode": skip when the element of A is zero, skip the empty blocks of the row
+ *       of B), found by AND-ing the bitmap row of A with the transposed B map.  Work grows with
+ *       the product of both densities, at a higher cost per product.  Reads X itself (not the
+ *       lists of the maps).  Needs ldy * sizeof(element) below 2^20 bytes; beyond that mmm_matmul
+ *       uses MATRIX whatever was asked for.
+ * Automatic choice (path -1): MATRIX if a tile variant has been fixed (mmm_maps_set_plan or the
+ * "matmul_variant" option).  Else, with p_A and p_B the densities of A's elements and B's
+ * blocks counted by the most recent mmm_maps_stats call on the handle (kept as the estimate
+ * across rebuilds): for matrices of at most 64 rows PAIRS unless p_A * p_B is known to exceed
+ * 0.02; for larger ones PAIRS iff the densities are known and p_B * (1 - 24.5 * p_A) > 0.035
+ * (A keeps fewer than 4 % of its elements and B is not nearly empty), else MATRIX.  The
+ * thresholds are fitted to timings on an MI355X.  The paper leaves this
+ * per-workload choice of method to the caller (section 6, choosing between methods by
+ * sparsity). */
+#define MMM_PATH_MATRIX 0
+#define MMM_PATH_PAIRS 1
+/* Fix the kernel for one handle (-1: automatic).  Errors: MMM_ERR_INVALID_ARG. */
+mmm_status mmm_maps_set_path(mmm_maps *maps, int32_t path);
+/* The kernel mmm_matmul would use now.  Errors: MMM_ERR_INVALID_ARG. */
+mmm_status mmm_matmul_path(const mmm_maps *maps, int32_t *path);
+
+/* C (+)= M(X) x B with the mask M evaluated inside the multiplication: the A-side pass of
+ * mmm_build_maps is not needed and X is read once (section 3 "Preprocessing": the cost of
+ * preprocessing matters for small matrices; rows of B are preprocessed once and reused).  Only
+ * the B side of the maps must have been built (for this Y, with element type dt); the A side of
+ * the maps is neither read nor written, so mmm_maps_view / mmm_maps_stats keep describing
+ * whatever mmm_build_maps last built.  Same definition of A as mmm_build_maps:
+ *     a_bits[i,k] = pred(X[i,k]) & keep_bits[i,k] & (X[i,k] != 0).
+ * Always uses the MMM_PATH_PAIRS kernel; meant for activations of few rows (decode), correct for
+ * any shape with ldy * sizeof(element) below 2^20 bytes.  Errors: MMM_ERR_INVALID_ARG (NULL
+ * pointer, bad pred, misaligned keep_bits), MMM_ERR_SHAPE (also: ldy beyond that), MMM_ERR_DTYPE, MMM_ERR_MAPS_MISMATCH (B side not built, or built for another
+ * element type), MMM_ERR_DEVICE. */
+mmm_status mmm_matmul_fused(const mmm_maps *maps, mmm_dtype dt,
+                            const void *X, int64_t ldx, const mmm_mask_a *ma,
+                            const void *Y, int64_t ldy,
+                            float *C, int64_t ldc, int32_t accumulate, void *hip_stream);
+
 /* The same multiplication for callers that cannot allocate and must not have
  * memory allocated on their behalf while they run: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  mmm_matmul keeps the
@@ -217,6 +259,7 @@ mmm_status mmm_matmul_static_scratch(const mmm_maps *maps, mmm_dtype dt,
 /* Process-wide tuning knobs (for benchmarking; the defaults choose by shape).
  *   "matmul_variant": -1 = automatic, else index of a compiled tile variant
  *   "split_k"       :  0 = automatic, else the number of K splits to use
+ *   "matmul_path"   : -1 = automatic, else MMM_PATH_MATRIX or MMM_PATH_PAIRS
  * Errors: MMM_ERR_INVALID_ARG (unknown name or value out of range). */
 mmm_status mmm_set_option(const char *name, int64_t value);
 

@@ -23,10 +23,12 @@ MMM_OK = 0
 MMM_ERR_INVALID_ARG, MMM_ERR_SHAPE, MMM_ERR_DTYPE, MMM_ERR_WORKSPACE, MMM_ERR_MAPS_MISMATCH, MMM_ERR_DEVICE = range(1, 7)
 MMM_F32, MMM_BF16, MMM_F16 = 0, 1, 2
 MMM_PRED_NONZERO, MMM_PRED_GT, MMM_PRED_ABS_GT = 0, 1, 2
+MMM_PATH_AUTO, MMM_PATH_MATRIX, MMM_PATH_PAIRS = -1, 0, 1
 
 EXPORTS = [
     "mmm_maps_workspace_bytes", "mmm_maps_init", "mmm_maps_release", "mmm_build_maps", "mmm_maps_view",
-    "mmm_maps_view_derived", "mmm_maps_view_lists", "mmm_maps_stats", "mmm_matmul", "mmm_matmul_static_scratch", "mmm_set_option", "mmm_matmul_variant_count",
+    "mmm_maps_view_derived", "mmm_maps_view_lists", "mmm_maps_stats", "mmm_matmul", "mmm_matmul_static_scratch", "mmm_matmul_fused",
+    "mmm_maps_set_path", "mmm_matmul_path", "mmm_set_option", "mmm_matmul_variant_count",
     "mmm_matmul_variant_name", "mmm_matmul_plan", "mmm_maps_set_plan", "mmm_status_string", "mmm_last_device_error",
 ]
 
@@ -67,6 +69,9 @@ def _load() -> ctypes.CDLL:
     lib.mmm_maps_stats.argtypes = [vp, c.POINTER(c.c_uint64), c.POINTER(c.c_uint64), c.POINTER(c.c_uint64), vp]
     lib.mmm_matmul.argtypes = [vp, i32, vp, i64, vp, i64, vp, i64, i32, vp]
     lib.mmm_matmul_static_scratch.argtypes = [vp, i32, vp, i64, vp, i64, vp, i64, i32, vp]
+    lib.mmm_matmul_fused.argtypes = [vp, i32, vp, i64, c.POINTER(MaskA), vp, i64, vp, i64, i32, vp]
+    lib.mmm_maps_set_path.argtypes = [vp, i32]
+    lib.mmm_matmul_path.argtypes = [vp, c.POINTER(i32)]
     lib.mmm_set_option.argtypes = [c.c_char_p, i64]
     lib.mmm_maps_set_plan.argtypes = [vp, i32, i32]
     lib.mmm_matmul_variant_count.restype = i32
@@ -179,6 +184,22 @@ def mmm_matmul_static_scratch(maps: int, dt: int, X, ldx: int, Y, ldy: int, C, l
                               stream=None) -> None:
     _check(lib.mmm_matmul_static_scratch(maps, dt, _ptr(X), ldx, _ptr(Y), ldy, _ptr(C), ldc, int(accumulate),
                                          _stream(stream)), "mmm_matmul_static_scratch")
+
+
+def mmm_matmul_fused(maps: int, dt: int, X, ldx: int, ma: MaskA, Y, ldy: int, C, ldc: int, accumulate: int = 0,
+                     stream=None) -> None:
+    _check(lib.mmm_matmul_fused(maps, dt, _ptr(X), ldx, ctypes.byref(ma), _ptr(Y), ldy, _ptr(C), ldc, int(accumulate),
+                                _stream(stream)), "mmm_matmul_fused")
+
+
+def mmm_maps_set_path(maps: int, path: int = -1) -> None:
+    _check(lib.mmm_maps_set_path(maps, int(path)), "mmm_maps_set_path")
+
+
+def mmm_matmul_path(maps: int) -> int:
+    v = ctypes.c_int32(0)
+    _check(lib.mmm_matmul_path(maps, ctypes.byref(v)), "mmm_matmul_path")
+    return v.value
 
 
 def mmm_maps_set_plan(maps: int, variant: int = -1, split_k: int = 0) -> None:

@@ -23,6 +23,7 @@ void note_device_error(const char *where, hipError_t e)
 
 std::atomic<int64_t> g_opt_variant{-1};
 std::atomic<int64_t> g_opt_split{0};
+std::atomic<int64_t> g_opt_path{-1};
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -118,6 +119,30 @@ mmm_plan make_plan(const mmm_maps *m, int32_t dt)
     return p;
 }
 
+// Which kernel multiplies.  The matrix-instruction kernel issues work in proportion to B's block
+// density (every listed row of B meets all rows of a tile of A); the pair kernel does work in
+// proportion to the product of both densities but pays two gathers per product and a fixed cost
+// per row and 64 columns.  Fitted to measurements on an MI355X (4096^3, 2048 x 16384 x 4096 and
+// 32 ... 512 x 8192 x 4096, densities 0.02 ... 0.4):
+//     pairs  ~ 130 us + 24500 us * p_A * p_B      matrix ~ 95 us + 1000 us * p_B      (per 4096^3)
+// so for matrices of many rows the pair kernel is ahead iff p_B * (1 - 24.5 * p_A) > 0.035, which
+// needs p_A below 0.04; for matrices of at most 64 rows (one tile of the matrix kernel, mostly
+// empty, and a latency-bound launch) it is ahead up to p_A * p_B of about 0.02.  Densities are
+// known only after a mmm_maps_stats call (the counts of the most recent one are kept as the
+// estimate, also across rebuilds: emergent sparsity levels are stable from step to step); without
+// one the shape decides alone.
+int32_t choose_path(const mmm_maps *m)
+{
+    int64_t path = m->plan_path >= 0 ? m->plan_path : g_opt_path.load();
+    if (path == MMM_PATH_MATRIX || path == MMM_PATH_PAIRS) return (int32_t)path;
+    if (m->plan_variant >= 0 || g_opt_variant.load() >= 0) return MMM_PATH_MATRIX;   // a tile variant was asked for
+    const bool known = m->stats_a_valid && m->stats_b_valid;
+    const double p_a = known ? (double)m->stats_nnz_a / ((double)m->M * (double)m->K) : 0.0;
+    const double p_b = known ? (double)m->stats_occ_b / ((double)m->K * (double)m->NB) : 0.0;
+    if (m->M <= 64) return !known || p_a * p_b <= 0.02 ? MMM_PATH_PAIRS : MMM_PATH_MATRIX;
+    return known && p_b * (1.0 - 24.5 * p_a) > 0.035 ? MMM_PATH_PAIRS : MMM_PATH_MATRIX;
+}
+
 }   // namespace
 
 extern "C" {
@@ -183,6 +208,9 @@ mmm_status mmm_maps_init(void *dev_workspace, size_t workspace_bytes, int64_t M,
     m->a_src_ld = 0;
     m->plan_variant = -1;
     m->plan_split = 0;
+    m->plan_path = -1;
+    m->stats_a_valid = m->stats_b_valid = false;
+    m->stats_nnz_a = m->stats_occ_b = 0;
     *out = m;
     return MMM_OK;
 }
@@ -286,6 +314,9 @@ mmm_status mmm_maps_stats(const mmm_maps *maps, uint64_t *nnz_a, uint64_t *occup
         note_device_error("statistics", e);
         return MMM_ERR_DEVICE;
     }
+    maps->stats_nnz_a = host[0];
+    maps->stats_occ_b = host[1];
+    maps->stats_a_valid = maps->stats_b_valid = true;
     if (nnz_a) *nnz_a = host[0];
     if (occupied_blocks_b) *occupied_blocks_b = host[1];
     if (useful_macs) *useful_macs = host[2];
@@ -320,6 +351,15 @@ static mmm_status matmul_common(const mmm_maps *maps, mmm_dtype dt, const void *
     if (maps->a_dtype != dt || maps->b_dtype != dt) return MMM_ERR_MAPS_MISMATCH;
     // the values of A travel in the lists that were copied from X at build time: another X is another A
     if (maps->a_src != X || maps->a_src_ld != ldx) return MMM_ERR_MAPS_MISMATCH;
+    if (choose_path(maps) == MMM_PATH_PAIRS && mmm_pairs_supports(dt, ldy)) {   // no scratch at all on this path
+        if (hipError_t e = mmm_launch_pairs(maps, dt, X, ldx, Y, ldy, C, ldc, accumulate ? 1 : 0, false, 0, 0.f, nullptr,
+                                            static_cast<hipStream_t>(hip_stream));
+            e != hipSuccess) {
+            note_device_error("masked GEMM (pairs) launch", e);
+            return MMM_ERR_DEVICE;
+        }
+        return MMM_OK;
+    }
     const mmm_plan p = make_plan(maps, dt);
     float *partials = maps->partials;
     size_t partial_bytes = maps->partial_bytes;
@@ -354,6 +394,30 @@ mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t
     return matmul_common(maps, dt, X, ldx, Y, ldy, C, ldc, accumulate, hip_stream, false);
 }
 
+mmm_status mmm_matmul_fused(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const mmm_mask_a *ma,
+                            const void *Y, int64_t ldy, float *C, int64_t ldc, int32_t accumulate, void *hip_stream)
+{
+    if (maps == nullptr || X == nullptr || Y == nullptr || C == nullptr || ma == nullptr) return MMM_ERR_INVALID_ARG;
+    if (ma->pred < MMM_PRED_NONZERO || ma->pred > MMM_PRED_ABS_GT) return MMM_ERR_INVALID_ARG;
+    if (ma->keep_bits != nullptr && reinterpret_cast<uintptr_t>(ma->keep_bits) % 8 != 0) return MMM_ERR_INVALID_ARG;
+    if (!dtype_ok(dt)) return MMM_ERR_DTYPE;
+    if (ldx < maps->K || ldy < maps->N || ldc < maps->N) return MMM_ERR_SHAPE;
+    if (ldx > kMaxLd || ldy > kMaxLd) return MMM_ERR_SHAPE;
+    const size_t esz = elem_size(dt);
+    if (reinterpret_cast<uintptr_t>(X) % esz != 0 || reinterpret_cast<uintptr_t>(Y) % esz != 0 ||
+        reinterpret_cast<uintptr_t>(C) % sizeof(float) != 0)
+        return MMM_ERR_DTYPE;
+    if (!mmm_pairs_supports(dt, ldy)) return MMM_ERR_SHAPE;
+    if (!maps->b_built || maps->b_dtype != dt) return MMM_ERR_MAPS_MISMATCH;
+    if (hipError_t e = mmm_launch_pairs(maps, dt, X, ldx, Y, ldy, C, ldc, accumulate ? 1 : 0, true, ma->pred,
+                                        ma->threshold, ma->keep_bits, static_cast<hipStream_t>(hip_stream));
+        e != hipSuccess) {
+        note_device_error("fused masked GEMM launch", e);
+        return MMM_ERR_DEVICE;
+    }
+    return MMM_OK;
+}
+
 mmm_status mmm_matmul_static_scratch(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const void *Y,
                                      int64_t ldy, float *C, int64_t ldc, int32_t accumulate, void *hip_stream)
 {
@@ -370,9 +434,29 @@ mmm_status mmm_maps_set_plan(mmm_maps *maps, int32_t variant, int32_t split_k)
     return MMM_OK;
 }
 
+mmm_status mmm_maps_set_path(mmm_maps *maps, int32_t path)
+{
+    if (maps == nullptr) return MMM_ERR_INVALID_ARG;
+    if (path < -1 || path > MMM_PATH_PAIRS) return MMM_ERR_INVALID_ARG;
+    maps->plan_path = path;
+    return MMM_OK;
+}
+
+mmm_status mmm_matmul_path(const mmm_maps *maps, int32_t *path)
+{
+    if (maps == nullptr || path == nullptr) return MMM_ERR_INVALID_ARG;
+    *path = choose_path(maps);
+    return MMM_OK;
+}
+
 mmm_status mmm_set_option(const char *name, int64_t value)
 {
     if (name == nullptr) return MMM_ERR_INVALID_ARG;
+    if (std::strcmp(name, "matmul_path") == 0) {
+        if (value < -1 || value > MMM_PATH_PAIRS) return MMM_ERR_INVALID_ARG;
+        g_opt_path.store(value);
+        return MMM_OK;
+    }
     if (std::strcmp(name, "matmul_variant") == 0) {
         if (value < -1 || value >= mmm_variant_count()) return MMM_ERR_INVALID_ARG;
         g_opt_variant.store(value);

@@ -56,7 +56,10 @@ struct mmm_maps {
     const void *a_src;   // address and leading dimension of the X the A side was built from (identity only)
     int64_t a_src_ld;
     // launch plan fixed for this handle (-1 / 0: none, follow the process-wide options)
-    int32_t plan_variant, plan_split;
+    int32_t plan_variant, plan_split, plan_path;
+    // what the most recent mmm_maps_stats call counted: the density estimate behind the choice of kernel
+    mutable bool stats_a_valid, stats_b_valid;
+    mutable uint64_t stats_nnz_a, stats_occ_b;
 };
 
 struct mmm_build_args {
@@ -96,5 +99,12 @@ const mmm_variant_info &mmm_variant(int32_t i);
 hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &p, int32_t dtype, const void *X, int64_t ldx,
                              const void *Y, int64_t ldy, float *C, int64_t ldc, int32_t accumulate, float *partials,
                              size_t partial_bytes, hipStream_t s);
+// The multiplication over exactly the surviving products, on the vector ALUs.  fused: evaluate M
+// (pred, threshold, keep_a) on X inside the kernel; otherwise a_bits of the maps are used.
+hipError_t mmm_launch_pairs(const mmm_maps *m, int32_t dtype, const void *X, int64_t ldx, const void *Y, int64_t ldy,
+                            float *C, int64_t ldc, int32_t accumulate, bool fused, int32_t pred, float threshold,
+                            const uint64_t *keep_a, hipStream_t s);
+// whether that kernel can address a Y of this leading dimension (it forms 32-bit offsets inside 4096 rows)
+bool mmm_pairs_supports(int32_t dtype, int64_t ldy);
 // device address of the library's own scratch array on the current device (MMM_STATIC_SCRATCH_BYTES bytes)
 hipError_t mmm_static_scratch(float **ptr);

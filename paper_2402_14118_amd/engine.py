@@ -54,6 +54,20 @@ class MaskedMatmul:
         B.mmm_matmul_static_scratch(self.maps, self.dtype, X, X.stride(0), Y, Y.stride(0), C, C.stride(0),
                                     int(accumulate), stream)
 
+    def matmul_fused(self, X: torch.Tensor, Y: torch.Tensor, C: torch.Tensor, pred: int = B.MMM_PRED_NONZERO,
+                     threshold: float = 0.0, keep_a: Optional[torch.Tensor] = None, accumulate: bool = False,
+                     stream=None) -> None:
+        """C (+)= M(X) x B with M evaluated inside the multiplication; only the B side of the maps is used."""
+        ma = B.MaskA(pred, threshold, B._ptr(keep_a))
+        B.mmm_matmul_fused(self.maps, self.dtype, X, X.stride(0), ma, Y, Y.stride(0), C, C.stride(0), int(accumulate),
+                           stream)
+
+    def set_path(self, path: int = -1) -> None:
+        B.mmm_maps_set_path(self.maps, path)
+
+    def path(self) -> int:
+        return B.mmm_matmul_path(self.maps)
+
     def stats(self, stream=None):
         return B.mmm_maps_stats(self.maps, stream)
 

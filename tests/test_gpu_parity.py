@@ -18,9 +18,18 @@ pytestmark = pytest.mark.gpu
 def _auto_options():
     mm.mmm_set_option("matmul_variant", -1)
     mm.mmm_set_option("split_k", 0)
+    mm.mmm_set_option("matmul_path", -1)
     yield
     mm.mmm_set_option("matmul_variant", -1)
     mm.mmm_set_option("split_k", 0)
+    mm.mmm_set_option("matmul_path", -1)
+
+
+@pytest.fixture(params=[mm.MMM_PATH_MATRIX, mm.MMM_PATH_PAIRS], ids=["matrix", "pairs"])
+def path(request):
+    """Runs a test once per multiplication kernel."""
+    mm.mmm_set_option("matmul_path", request.param)
+    return request.param
 
 
 def derived_from_bits(ab, bb, M, K, NB):
@@ -89,13 +98,13 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("M,K,N,bw", SHAPES)
-def test_small_shapes_exact_integers(M, K, N, bw):
+def test_small_shapes_exact_integers(M, K, N, bw, path):
     w = synth.random_masked(M, K, N, bw, 0.3, 0.4, 500 + M + K, dist="smallint", p_rows=0.8)
     check_workload(w, f"int {M}x{K}x{N} bw{bw}", exact=True)
 
 
 @pytest.mark.parametrize("M,K,N,bw", SHAPES[3:])
-def test_small_shapes_float(M, K, N, bw):
+def test_small_shapes_float(M, K, N, bw, path):
     w = synth.random_masked(M, K, N, bw, 0.25, 0.3, 900 + N, dist="normal")
     check_workload(w, f"f32 {M}x{K}x{N} bw{bw}")
 
@@ -125,7 +134,7 @@ def test_long_k_dense_lists(variant, bw, p_a, p_b):
 
 
 @pytest.mark.parametrize("bw", [8, 16, 32])
-def test_column_structured_a(bw):
+def test_column_structured_a(bw, path):
     """Whole columns of A and the same rows of B switched off: the k lists shrink to the shared set."""
     w = synth.column_sparse(130, 1000, 320, bw, 0.15, 0.7, 0.8, 600 + bw)
     run, (ab, bb, *_rest) = check_workload(w, f"column sparse bw {bw}")
@@ -134,7 +143,7 @@ def test_column_structured_a(bw):
     assert not (synth.unpack_bits(bb, w.N // bw).any(axis=1) & ~selected).any()
 
 
-def test_padded_leading_dimensions_and_unaligned_rows():
+def test_padded_leading_dimensions_and_unaligned_rows(path):
     w = synth.random_masked(70, 203, 80, 16, 0.3, 0.5, 31, dist="smallint")
     check_workload(w, "ld padded", exact=True, ldx=209, ldy=83, ldc=91)
 
@@ -170,7 +179,7 @@ def test_predicates_and_special_values():
 
 @pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16, synth.DT_F16])
 @pytest.mark.parametrize("bw,N", [(8, 136), (16, 128), (32, 160)])
-def test_masked_positions_may_hold_anything(bw, N, dtype):
+def test_masked_positions_may_hold_anything(bw, N, dtype, path):
     """Masked-out X elements and switched-off Y blocks never reach the arithmetic.  With bw = 8 a 16-column group of
     the multiplier spans two blocks (and N = 136 leaves half a group at the edge), with bw = 32 a block spans two
     groups."""
@@ -191,7 +200,7 @@ def test_masked_positions_may_hold_anything(bw, N, dtype):
 
 
 @pytest.mark.parametrize("bw", [8, 16, 32])
-def test_non_finite_value_inside_an_occupied_block(bw):
+def test_non_finite_value_inside_an_occupied_block(bw, path):
     """The stated contract for a kept Inf in Y: only its column of C is affected; rows whose element of A at that k is
     non-zero get a non-finite result, the other rows of that column the exact value or NaN."""
     w = synth.random_masked(100, 300, 160, bw, 0.3, 0.5, 41 + bw, dist="smallint")
@@ -225,7 +234,7 @@ def test_matmul_refuses_another_x_than_the_one_built_from():
     run.matmul()          # the X it was built from is accepted
 
 
-def test_identity_zero_and_full_masks():
+def test_identity_zero_and_full_masks(path):
     n, bw = 96, 16
     rng = np.random.default_rng(2)
     Y = rng.standard_normal((n, n)).astype(np.float32)
@@ -249,7 +258,7 @@ def test_identity_zero_and_full_masks():
     assert np.all(np.abs(C - ref) <= 1e-5 * mag + 1e-6)
 
 
-def test_accumulate_and_cached_b_map():
+def test_accumulate_and_cached_b_map(path):
     w = synth.random_masked(90, 300, 160, 16, 0.3, 0.3, 21, dist="smallint")
     ab, bb, C_ref, _ = oracle.run_workload(w)
     run = HipRun(w)
@@ -301,6 +310,93 @@ def test_16_bit_inputs_every_variant(variant, dtype):
     check_workload(w, f"dtype {dtype} variant {variant}", exact=True)
 
 
+# ---- the kernel over exactly the surviving products (vector FMAs) -----------------------------
+@pytest.mark.parametrize("bw,p_a,p_b", [(16, 0.9, 0.95), (8, 0.15, 0.5), (32, 0.5, 0.1), (8, 1.0, 1.0)])
+@pytest.mark.parametrize("M,N", [(5, 96), (300, 2048)])
+def test_pairs_long_k_dense_lists(bw, p_a, p_b, M, N):
+    """K beyond one range of the row copy in LDS; lists far longer than one pass holds (dense A and B); both workgroup
+    shapes (few rows: every range of k is split over four waves; many rows: eight waves side by side)."""
+    mm.mmm_set_option("matmul_path", mm.MMM_PATH_PAIRS)
+    w = synth.random_masked(M, 20000, N, bw, p_a, p_b, 5150 + bw + M, dist="smallint")
+    check_workload(w, f"pairs long K bw {bw} M {M}", exact=True)
+
+
+def test_automatic_path():
+    """Few rows: the pair kernel.  Many rows: the matrix kernel until the statistics show a very sparse A."""
+    w = synth.random_masked(40, 300, 64, 16, 0.3, 0.3, 1)
+    run = HipRun(w)
+    run.build()
+    assert run.eng.path() == mm.MMM_PATH_PAIRS
+    run.eng.set_plan(0, 1)
+    assert run.eng.path() == mm.MMM_PATH_MATRIX       # a tile variant was asked for
+    run.eng.set_plan()
+    for p_a, p_b, want in [(0.02, 0.3, mm.MMM_PATH_PAIRS), (0.02, 0.02, mm.MMM_PATH_MATRIX), (0.2, 0.3, mm.MMM_PATH_MATRIX)]:
+        w = synth.random_masked(200, 600, 128, 16, p_a, p_b, 2, dist="smallint")
+        run = HipRun(w)
+        run.build()
+        assert run.eng.path() == mm.MMM_PATH_MATRIX   # nothing counted yet
+        run.eng.stats()
+        assert run.eng.path() == want
+        run.build()                                    # the estimate survives a rebuild
+        assert run.eng.path() == want
+        run.matmul()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(run.C.cpu().numpy(), oracle.run_workload(w)[2])
+        run.eng.set_path(mm.MMM_PATH_MATRIX)
+        assert run.eng.path() == mm.MMM_PATH_MATRIX
+        run.eng.set_path()
+
+
+FUSED_CASES = [(synth.PRED_NONZERO, 0.0, True), (synth.PRED_GT, 0.0, False), (synth.PRED_GT, -0.5, True),
+               (synth.PRED_ABS_GT, 0.7, False), (synth.PRED_GT, 1e-40, False)]
+
+
+@pytest.mark.parametrize("pred,thr,with_keep", FUSED_CASES)
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16, synth.DT_F16])
+def test_fused_mask_evaluation(pred, thr, with_keep, dtype):
+    """mmm_matmul_fused: M is evaluated inside the multiplication (predicate, keep bitmap, non-zero test), only the B
+    side of the maps is built.  Special values in X as in the builder's test; C against the oracle."""
+    rng = np.random.default_rng(77)
+    M, K, N, bw = 37, 9000, 208, 16
+    w = synth.random_masked(M, K, N, bw, 0.4, 0.4, 4040, dist="normal", dtype=dtype)
+    w.X[0, :8] = [0.0, -0.0, 1e-45, -1e-40, 3e-39, -2.0, 0.5, 1.0]
+    w.X[1, 5] = np.nan if pred != synth.PRED_NONZERO else 1.0
+    if dtype == synth.DT_BF16:
+        w.X_bits, w.X = synth.round_to_bf16(w.X)
+    elif dtype == synth.DT_F16:
+        w.X_bits, w.X = synth.round_to_f16(w.X)
+    w.pred, w.threshold = pred, thr
+    if not with_keep:
+        w.keep_a = None
+    ab, bb, C_ref, mag = oracle.run_workload(w)
+    run = HipRun(w)
+    run.build(a=False, b=True)
+    run.eng.matmul_fused(run.X, run.Y, run.C, pred, thr, run.keep_a)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(run.maps_host()[1], bb)
+    assert_close(run.C.cpu().numpy(), C_ref, mag, dtype, f"fused pred {pred} thr {thr}")
+    run.eng.matmul_fused(run.X, run.Y, run.C, pred, thr, run.keep_a, accumulate=True)
+    torch.cuda.synchronize()
+    assert_close(run.C.cpu().numpy(), 2 * C_ref, 2 * mag, dtype, "fused accumulate")
+
+
+def test_fused_exact_and_argument_checks():
+    w = synth.random_masked(70, 700, 144, 8, 0.3, 0.4, 99, dist="smallint")
+    _, _, C_ref, _ = oracle.run_workload(w)
+    run = HipRun(w, ldx=711, ldy=150, ldc=149)
+    with pytest.raises(mm.MmmError) as e:
+        run.eng.matmul_fused(run.X, run.Y, run.C, w.pred, w.threshold, run.keep_a)      # B side not built
+    assert e.value.status == mm.binding.MMM_ERR_MAPS_MISMATCH
+    run.build(a=False, b=True)
+    run.eng.matmul_fused(run.X, run.Y, run.C, w.pred, w.threshold, run.keep_a)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(run.C.cpu().numpy(), C_ref)
+    assert torch.isnan(run.Cbuf[:, w.N:]).all()
+    with pytest.raises(mm.MmmError) as e:
+        run.eng.matmul_fused(run.X, run.Y, run.C, 3, 0.0, None)
+    assert e.value.status == mm.binding.MMM_ERR_INVALID_ARG
+
+
 def test_autotune_fixes_a_plan_and_keeps_the_result():
     w = synth.random_masked(130, 900, 384, 16, 0.2, 0.2, 808, dist="smallint")
     _, _, C_ref, _ = oracle.run_workload(w)
@@ -329,14 +425,14 @@ def test_run_to_run_bitwise_reproducible():
 
 
 @pytest.mark.parametrize("dtype", [synth.DT_BF16, synth.DT_F16])
-def test_16_bit_inputs_small(dtype):
+def test_16_bit_inputs_small(dtype, path):
     w = synth.random_masked(32, 520, 96, 16, 0.3, 0.3, 17, dist="normal", dtype=dtype)
     check_workload(w, f"dtype {dtype} small")
     w = synth.random_masked(45, 260, 64, 8, 0.3, 0.3, 18, dist="smallint", dtype=dtype)
     check_workload(w, f"dtype {dtype} int", exact=True)
 
 
-def test_f16_predicates_and_tiny_values():
+def test_f16_predicates_and_tiny_values(path):
     """Half-precision denormals are non-zero and widen exactly; ReLU-style and magnitude predicates act on the value."""
     rng = np.random.default_rng(5)
     M, K, N, bw = 40, 200, 64, 16
@@ -365,13 +461,16 @@ def test_random_shapes_sweep():
         p_a, p_b = (float(rng.choice([0.02, 0.1, 0.3, 0.7, 1.0])) for _ in range(2))
         dtype = int(rng.choice([synth.DT_F32, synth.DT_BF16, synth.DT_F16]))
         variant, split = int(rng.integers(-1, nv)), int(rng.integers(0, 5))
+        path, fused = int(rng.integers(-1, 2)), bool(rng.random() < 0.25)
         if variant >= 0 and mm.mmm_matmul_variant_name(variant).startswith("R2") and M > 32:
             variant = -1
         ld = dict(ldx=K + int(rng.integers(0, 9)), ldy=N + int(rng.integers(0, 9)), ldc=N + int(rng.integers(0, 9)))
-        what = f"sweep {it}: M={M} K={K} N={N} bw={bw} p_a={p_a} p_b={p_b} dtype={dtype} variant={variant} split={split} {ld}"
+        what = (f"sweep {it}: M={M} K={K} N={N} bw={bw} p_a={p_a} p_b={p_b} dtype={dtype} variant={variant} split={split} "
+                f"path={path} fused={fused} {ld}")
         print(what, flush=True)
         mm.mmm_set_option("matmul_variant", variant)
         mm.mmm_set_option("split_k", split)
+        mm.mmm_set_option("matmul_path", path)
         w = synth.random_masked(M, K, N, bw, p_a, p_b, 20000 + it, dist="smallint", dtype=dtype)
         ab, bb, C_ref, _ = oracle.run_workload(w)
         run = HipRun(w, **ld)
@@ -380,31 +479,37 @@ def test_random_shapes_sweep():
         np.testing.assert_array_equal(b_hip, bb, err_msg=what)
         np.testing.assert_array_equal(C, C_ref, err_msg=what)
         assert torch.isnan(run.Cbuf[:, N:]).all(), what
+        if fused:
+            run.Cbuf.fill_(float("nan"))
+            run.eng.matmul_fused(run.X, run.Y, run.C, w.pred, w.threshold, run.keep_a)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(run.C.cpu().numpy(), C_ref, err_msg=what + " (fused)")
+            assert torch.isnan(run.Cbuf[:, N:]).all(), what
 
 
 # ---- the benchmark configurations at full size ------------------------------------------------
-def test_config1_full():
+def test_config1_full(path):
     check_workload(synth.config(1), "config 1")
 
 
-def test_config2_full():
+def test_config2_full(path):
     run, _ = check_workload(synth.config(2), "config 2")
     print("plan", run.eng.plan())
 
 
-def test_config5_full_bf16_decode():
+def test_config5_full_bf16_decode(path):
     run, _ = check_workload(synth.config(5), "config 5")
     print("plan", run.eng.plan())
 
 
 @pytest.mark.parametrize("ip", range(len(synth.SWEEP_P)))
-def test_config3_full(ip):
+def test_config3_full(ip, path):
     """Every point of the sparsity sweep at full size, in the launch configuration the benchmark times, element by
     element against the oracle."""
     run, _ = check_workload(synth.config(3, ip), f"config 3 p={synth.SWEEP_P[ip]}")
     print("plan", run.eng.plan(), flush=True)
 
 
-def test_config4_full():
+def test_config4_full(path):
     run, _ = check_workload(synth.config(4), "config 4")
     print("plan", run.eng.plan(), flush=True)

@@ -32,6 +32,7 @@ def _both(w, accumulate=False):
 def test_static_scratch_matches_matmul_twice_in_a_row():
     mm.mmm_set_option("matmul_variant", -1)
     mm.mmm_set_option("split_k", 0)
+    mm.mmm_set_option("matmul_path", mm.MMM_PATH_MATRIX)      # the kernel that splits K and needs the scratch
     # decode-like shapes: few tiles of C and a long K, so the plan splits K and the partial sums are used
     w1 = synth.random_masked(32, 8192, 512, 16, 0.1, 0.2, 901, dist="normal")
     run, want, got = _both(w1)
@@ -48,6 +49,7 @@ def test_static_scratch_matches_matmul_twice_in_a_row():
 
 
 def test_static_scratch_without_a_split_and_beyond_its_size():
+    mm.mmm_set_option("matmul_path", mm.MMM_PATH_MATRIX)
     w = synth.random_masked(150, 300, 400, 16, 0.3, 0.3, 903, dist="smallint")       # plan does not split K: no scratch
     run, want, got = _both(w)
     assert run.eng.plan()[1] == 1
@@ -67,3 +69,9 @@ def test_static_scratch_without_a_split_and_beyond_its_size():
     torch.cuda.synchronize()
     _, _, C_ref, _ = oracle.run_workload(w)
     np.testing.assert_array_equal(run.C.cpu().numpy(), C_ref)
+
+
+@pytest.fixture(autouse=True)
+def _reset_path():
+    yield
+    mm.mmm_set_option("matmul_path", -1)
