@@ -100,8 +100,9 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
 
     build()
     matmul()
-    nnz_a, occ_b, useful_macs = eng.stats()
+    nnz_a, occ_b, useful_macs = eng.stats()     # also gives the library its density estimate for the choice of kernel
     variant, split_k, workgroups = eng.plan()
+    path = eng.path()
 
     for _ in range(warmup):
         build()
@@ -136,6 +137,16 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
         matmul()
     torch.cuda.synchronize()
     ms_cached = (time.perf_counter() - t0) * 1e3 / K
+
+    # and with the A mask evaluated inside the multiplication (one launch per step, B side cached)
+    for _ in range(min(warmup, 5)):
+        eng.matmul_fused(X, Y, C, w.pred, w.threshold, keep_a)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        eng.matmul_fused(X, Y, C, w.pred, w.threshold, keep_a)
+    torch.cuda.synchronize()
+    ms_fused = (time.perf_counter() - t0) * 1e3 / K
 
     out_trials = None
     if trials:   # the paper's protocol beside it: 10 trials of 20 steps each, median and minimum
@@ -200,7 +211,8 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
 
     useful_flops = 2.0 * useful_macs
     dense_flops = 2.0 * w.M * w.K * w.N
-    issued_flops = 2.0 * w.M * occ_b * w.bw      # every occupied block of B against all rows of A (matrix path)
+    # matrix path: every occupied block of B against all rows of A; pair path: the surviving products only
+    issued_flops = 2.0 * w.M * occ_b * w.bw if path == mm.MMM_PATH_MATRIX else useful_flops
 
     # algorithmic bytes of one launch: what the method itself must move (lists, occupied blocks, maps, C)
     WA, NB = (w.K + 63) // 64, w.N // w.bw
@@ -237,10 +249,11 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
 
     rb = floors(build_bytes, 0.0, t_build)
     rm = floors(matmul_bytes, useful_flops, t_matmul)
-    rm["issued_matrix_TFLOPs"] = issued_flops / (t_matmul * 1e-3) / 1e12
-    rm["issued_frac_of_fp32_matrix_peak"] = rm["issued_matrix_TFLOPs"] / FP32_MFMA_PEAK_TFLOPS
+    rm["issued_TFLOPs"] = issued_flops / (t_matmul * 1e-3) / 1e12
+    rm["issued_frac_of_fp32_peak"] = rm["issued_TFLOPs"] / FP32_MFMA_PEAK_TFLOPS
     rm["useful_over_issued"] = useful_flops / issued_flops if issued_flops else None
-    dom_name, dom = ("mmm_matmul_kernel", rm) if t_matmul >= t_build else ("mmm_build_kernel", rb)
+    mm_kernel = "mmm_matmul_kernel" if path == mm.MMM_PATH_MATRIX else "mmm_pairs_kernel"
+    dom_name, dom = (mm_kernel, rm) if t_matmul >= t_build else ("mmm_build_kernel", rb)
     if dom["bound"] == "alu":
         roofline = {"bound": "alu", "achieved": dom["achieved_TFLOPs"], "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
     else:
@@ -254,14 +267,17 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
         "dtype": {synth.DT_F32: "f32", synth.DT_BF16: "bf16", synth.DT_F16: "f16"}[w.dtype],
         "nnz_a": nnz_a, "occupied_blocks_b": occ_b, "useful_macs": useful_macs,
         "a_density": nnz_a / (w.M * w.K), "b_block_density": occ_b / (w.K * NB),
-        "variant": mm.mmm_matmul_variant_name(variant), "split_k": split_k, "workgroups": workgroups,
+        "path": "matrix" if path == mm.MMM_PATH_MATRIX else "pairs",
+        "variant": mm.mmm_matmul_variant_name(variant) if path == mm.MMM_PATH_MATRIX else None,
+        "split_k": split_k if path == mm.MMM_PATH_MATRIX else None, "workgroups": workgroups,
         "steps": K, "step_us": ms_per_step * 1e3, "build_us": t_build * 1e3, "matmul_us": t_matmul * 1e3,
         "useful_gflops": useful_flops / (ms_per_step * 1e-3) / 1e9,
         "useful_gflops_matmul_only": useful_flops / (t_matmul * 1e-3) / 1e9,
         "dense_equivalent_gflops": dense_flops / (ms_per_step * 1e-3) / 1e9,
         "dense_equivalent_gflops_matmul_only": dense_flops / (t_matmul * 1e-3) / 1e9,
         "cached_b": {"step_us": ms_cached * 1e3, "build_a_us": t_build_a * 1e3,
-                     "useful_gflops": useful_flops / (ms_cached * 1e-3) / 1e9},
+                     "useful_gflops": useful_flops / (ms_cached * 1e-3) / 1e9,
+                     "fused_step_us": ms_fused * 1e3},
         "roofline": roofline,
     }
     if out_trials:
@@ -304,6 +320,7 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
         row["speedup_vs_dense"] = t_dense / ms_per_step
         row["speedup_vs_dense_matmul_only"] = t_dense / t_matmul
         row["cached_b"]["speedup_vs_dense"] = t_dense / ms_cached
+        row["cached_b"]["fused_speedup_vs_dense"] = t_dense / ms_fused
         del A, B, D
     eng.close()
     del eng, X, Y, C, keep_a, keep_rows, keep_blocks
@@ -357,7 +374,7 @@ def cpu_baseline(w):
     return out
 
 
-SLIM_KEYS = ("workload", "a_density", "b_block_density", "variant", "split_k", "step_us", "build_us", "matmul_us",
+SLIM_KEYS = ("workload", "a_density", "b_block_density", "path", "variant", "split_k", "step_us", "build_us", "matmul_us",
              "useful_gflops", "useful_gflops_matmul_only", "dense_equivalent_gflops", "dense_gemm_us",
              "speedup_vs_dense", "speedup_vs_dense_matmul_only", "cached_b", "roofline")
 
@@ -437,9 +454,10 @@ def main():
         "config": {"workload": label, "M": head["M"], "K": head["K"], "N": head["N"], "block_width": head["block_width"],
                    "nnz_a": head["nnz_a"], "occupied_blocks_b": head["occupied_blocks_b"],
                    "useful_macs": head["useful_macs"], "a_density": head["a_density"],
-                   "b_block_density": head["b_block_density"], "variant": head["variant"],
+                   "b_block_density": head["b_block_density"], "path": head["path"], "variant": head["variant"],
                    "split_k": head["split_k"], "workgroups": head["workgroups"]},
-        "step": "mmm_build_maps (both sides) + mmm_matmul; cached_b = the A side only + mmm_matmul",
+        "step": "mmm_build_maps (both sides) + mmm_matmul; cached_b.step_us = the A side only + mmm_matmul; "
+                "cached_b.fused_step_us = mmm_matmul_fused alone (A mask evaluated inside the multiplication)",
         "dense_equivalent_gflops": head["dense_equivalent_gflops"],
         "t_build_us": head["build_us"], "t_matmul_us": head["matmul_us"],
         "kernel_timing": "second pass of the same steps with a HIP event after every launch",
