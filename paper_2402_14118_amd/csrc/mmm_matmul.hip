@@ -70,6 +70,35 @@ struct MatmulParams {
     int32_t accumulate;
 };
 
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+
+// 16-bit inputs are contracted by the matrix instructions of their own type, 16 values of k per
+// instruction (fp32 accumulate).  Operands reach the multiply step widened to float (the slab and
+// the lists of A hold float bit patterns); two of them are narrowed back into one register here,
+// which is exact because they were widened from that type.
+template <typename T> struct Narrow;
+template <> struct Narrow<uint16_t> {   // bf16: the upper halves of the two float patterns
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi)
+    {
+        return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+    }
+    static __device__ __forceinline__ floatx4 mfma(uint2 a, uint2 b, floatx4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, a), __builtin_bit_cast(shortx4, b), c, 0, 0, 0);
+    }
+};
+template <> struct Narrow<_Float16> {
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi)
+    {
+        return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+    }
+    static __device__ __forceinline__ floatx4 mfma(uint2 a, uint2 b, floatx4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(halfx4, a), __builtin_bit_cast(halfx4, b), c, 0, 0, 0);
+    }
+};
+
 template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f32<uint16_t>(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }   // bf16
@@ -339,6 +368,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     };
     // the quads of one batch that hold a live k: `left` live k from the batch's first slot on
     auto mfma_batch = [&](int g, const avec (&a)[QB], const float (&b)[QB], int left) __attribute__((always_inline)) {
+        if constexpr (sizeof(T) == 2) {
+            // One 16x16x16 instruction per row tile takes the whole batch: element u of a lane's operand
+            // is list slot 4 * u + s, for A and B alike.  Slots without a live k hold the slab's zero
+            // column on the A side and a re-read row on the B side, so they add nothing.
+            const uint2 bp = make_uint2(Narrow<T>::pack(b[0], b[1]), Narrow<T>::pack(b[2], b[3]));
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                const uint2 ap = make_uint2(Narrow<T>::pack(a[0][r], a[1][r]), Narrow<T>::pack(a[2][r], a[3][r]));
+                acc[g][r] = Narrow<T>::mfma(ap, bp, acc[g][r]);
+            }
+            return;
+        }
         mfma_quad(g, a[0], b[0]);
         if (left > 4) {
             mfma_quad(g, a[1], b[1]);
