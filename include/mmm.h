@@ -126,7 +126,8 @@ void mmm_maps_release(mmm_maps *maps);
  * Y == NULL: that side's maps from an earlier call are kept -- the B side of a
  * weight matrix is built once and reused (section 3: rows of B are preprocessed
  * once and used many times).  Lanes of Y whose block is switched off by the keep
- * bitmaps are not read.
+ * bitmaps are not read.  With mb->keep_rows the B side is built in row-compacted
+ * mode (see mmm_maps_view_compacted), which ties the lists of A to this B side.
  * Errors: MMM_ERR_INVALID_ARG (maps NULL, both X and Y NULL, mask struct NULL for
  * a present side, bad pred), MMM_ERR_SHAPE (ld too small, block_width differs
  * from the handle's), MMM_ERR_DTYPE, MMM_ERR_DEVICE. */
@@ -149,6 +150,27 @@ mmm_status mmm_maps_view(const mmm_maps *maps, const uint64_t **a_bits, int64_t 
 mmm_status mmm_maps_view_derived(const mmm_maps *maps, const uint64_t **a_colany, const uint64_t **bt_bits,
                                  int64_t *k_words);
 
+/* Row-compacted mode.  When mmm_build_maps is given mb->keep_rows (whole rows of Y switched off:
+ * the contextual selection of neurons of section 4 "Matrices from ML workloads"), the rows that
+ * keep_rows leaves on are numbered k' = 0 .. K'-1 in ascending k, and the matrix kernel walks k'
+ * in steps of 128 live rows instead of walking k in steps of 128 rows of which few are live.  The
+ * builder then also writes, for the multiplication and for inspection here:
+ *   *live_count : device pointer to K' (one uint32)
+ *   kmap        : K' entries, kmap[k'] = k
+ *   a_colany_c  : ceil(M/32) x ceil(K/64) words; bit k' of row t = OR of a_bits[i, kmap[k']], i in [32t, 32t+32)
+ *   btc_bits    : NB x ceil(K/64) words; bit k' of row jb = b_bits[kmap[k'], jb]
+ *   (bits k' >= K' up to the next multiple of 128 are zero; words beyond are unspecified)
+ * and keeps a copy of the kept blocks of the live rows of Y (row k' of the copy = row kmap[k'] of
+ * Y), from which the matrix kernel takes B; Y itself is still what MMM_PATH_PAIRS and
+ * mmm_matmul_fused read.  The blocked lists of A (mmm_maps_view_lists) are then over k' as well.
+ * *on says whether the B side was last built this way.  Because the lists of A depend on the
+ * numbering, building the B side alone (X == NULL) with keep_rows, or after it had been built with
+ * keep_rows, leaves the A side unbuilt: build A in the same call or afterwards.
+ * Any out pointer may be NULL.  Errors: MMM_ERR_INVALID_ARG. */
+mmm_status mmm_maps_view_compacted(const mmm_maps *maps, int32_t *on, const uint32_t **live_count,
+                                   const uint32_t **kmap, const uint64_t **a_colany_c,
+                                   const uint64_t **btc_bits);
+
 /* Device pointers to the blocked non-zero lists of A, for inspection.  A is cut
  * into *blocks_m x *blocks_k blocks of 64 rows x 128 columns (ragged at the far
  * edges); block (bm, bk) has index bm * *blocks_k + bk.
@@ -159,6 +181,9 @@ mmm_status mmm_maps_view_derived(const mmm_maps *maps, const uint64_t **a_colany
  *       high 32 bits = the value as IEEE float bits (16-bit types widened)
  *     then words {34816, 0} up to the next multiple of 64 (none if the count
  *     is one already); words beyond that are unspecified.
+ * In row-compacted mode (see mmm_maps_view_compacted) the columns are the live columns k': block
+ * (bm, bk) holds k' in [128 bk, 128 bk + 128), column_in_block = k' - 128 bk, and only the blocks
+ * with 128 bk < K' are written.
  * Errors: MMM_ERR_INVALID_ARG. */
 mmm_status mmm_maps_view_lists(const mmm_maps *maps, const uint32_t **counts, const uint64_t **entries,
                                int64_t *blocks_m, int64_t *blocks_k, int64_t *capacity);

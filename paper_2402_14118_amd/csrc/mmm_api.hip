@@ -28,7 +28,7 @@ std::atomic<int64_t> g_opt_path{-1};
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t a_bits, a_colany, a_cnt, a_ent, b_bits, bt_bits, stats, partials, partial_bytes, total;
+    size_t a_bits, a_colany, a_cnt, a_ent, b_bits, bt_bits, stats, kinfo, kmap, a_colany_c, btc_bits, Bc, partials, partial_bytes, total;
 };
 
 bool shape_ok(int64_t M, int64_t K, int64_t N, int32_t bw)
@@ -61,6 +61,17 @@ Layout make_layout(int64_t M, int64_t K, int64_t N, int32_t bw)
     off += align_up((size_t)NB * WA * 8);
     l.stats = off;
     off += align_up(4 * 8);
+    // row-compacted mode: numbering of the live rows, maps over it, and room for every row of Y in its widest type
+    l.kinfo = off;
+    off += align_up(64);
+    l.kmap = off;
+    off += align_up((size_t)K * 4);
+    l.a_colany_c = off;
+    off += align_up((size_t)MT * WA * 8);
+    l.btc_bits = off;
+    off += align_up((size_t)NB * WA * 8);
+    l.Bc = off;
+    off += align_up((size_t)K * (size_t)N * 4);
     l.partials = off;
     // room for up to 32 splits of C, capped
     size_t want = (size_t)M * (size_t)N * sizeof(float) * 32;
@@ -198,11 +209,17 @@ mmm_status mmm_maps_init(void *dev_workspace, size_t workspace_bytes, int64_t M,
     m->b_bits = reinterpret_cast<uint64_t *>(base + l.b_bits);
     m->bt_bits = reinterpret_cast<uint64_t *>(base + l.bt_bits);
     m->stats = reinterpret_cast<uint64_t *>(base + l.stats);
+    m->kinfo = reinterpret_cast<uint32_t *>(base + l.kinfo);
+    m->kmap = reinterpret_cast<uint32_t *>(base + l.kmap);
+    m->a_colany_c = reinterpret_cast<uint64_t *>(base + l.a_colany_c);
+    m->btc_bits = reinterpret_cast<uint64_t *>(base + l.btc_bits);
+    m->Bc = base + l.Bc;
     m->partials = reinterpret_cast<float *>(base + l.partials);
     m->partial_bytes = l.partial_bytes;
     m->ws = dev_workspace;
     m->ws_bytes = workspace_bytes;
     m->a_built = m->b_built = false;
+    m->a_compact = m->b_compact = false;
     m->a_dtype = m->b_dtype = -1;
     m->a_src = nullptr;
     m->a_src_ld = 0;
@@ -250,11 +267,23 @@ mmm_status mmm_build_maps(mmm_maps *maps, mmm_dtype dt, const void *X, int64_t l
         a.keep_rows = mb->keep_rows;
         a.keep_blocks = mb->keep_blocks;
     }
+    // Row-compacted mode: when keep_rows switches whole rows of B off, the live rows are numbered k' and the
+    // matrix kernel walks k' (steps of 128 live rows instead of 128 rows of which few are live).  The lists of
+    // A are then made over k', so they are only good for the numbering they were made for.
+    a.b_compact = Y != nullptr && mb->keep_rows != nullptr;
+    const bool compact_after = Y != nullptr ? a.b_compact : maps->b_compact;
+    a.a_compact = X != nullptr && compact_after;
     if (hipError_t e = mmm_launch_build(maps, a, static_cast<hipStream_t>(hip_stream)); e != hipSuccess) {
         note_device_error("map builder launch", e);
         return MMM_ERR_DEVICE;
     }
+    if (Y != nullptr) {
+        // lists of A made for another numbering of k (or for none) do not fit the new B side
+        if (X == nullptr && (maps->b_compact || a.b_compact)) maps->a_built = false;
+        maps->b_compact = a.b_compact;
+    }
     if (X != nullptr) {
+        maps->a_compact = a.a_compact;
         maps->a_built = true;
         maps->a_dtype = dt;
         maps->a_src = X;   // compared, never dereferenced
@@ -285,6 +314,18 @@ mmm_status mmm_maps_view_derived(const mmm_maps *maps, const uint64_t **a_colany
     if (a_colany) *a_colany = maps->a_colany;
     if (bt_bits) *bt_bits = maps->bt_bits;
     if (k_words) *k_words = maps->WA;
+    return MMM_OK;
+}
+
+mmm_status mmm_maps_view_compacted(const mmm_maps *maps, int32_t *on, const uint32_t **live_count, const uint32_t **kmap,
+                                   const uint64_t **a_colany_c, const uint64_t **btc_bits)
+{
+    if (maps == nullptr) return MMM_ERR_INVALID_ARG;
+    if (on) *on = maps->b_compact ? 1 : 0;
+    if (live_count) *live_count = maps->kinfo;
+    if (kmap) *kmap = maps->kmap;
+    if (a_colany_c) *a_colany_c = maps->a_colany_c;
+    if (btc_bits) *btc_bits = maps->btc_bits;
     return MMM_OK;
 }
 

@@ -41,7 +41,15 @@ struct BuildParams {
     int64_t M, K, N, NB, WA, WB, MT, KBA;
     uint32_t thr_bits;
     int32_t pred;
-    uint32_t n_a;   // workgroups that scan X
+    uint32_t n_a;    // workgroups that scan X block by block (bitmaps and, unless row-compacted, lists)
+    uint32_t n_ac;   // row-compacted mode: workgroups that list the blocks of A over the live k only
+    uint32_t n_b;    // workgroups that scan Y
+    // row-compacted mode (whole rows of B switched off by keep_rows): k' = 0 .. *kinfo - 1 numbers the live rows
+    const uint32_t *kinfo;   // [0] = number of live k
+    const uint32_t *kmap;    // k' -> k
+    uint64_t *a_colany_c;    // column-any words of A over k'
+    uint16_t *btc_pieces;    // transposed B map over k'
+    void *Bc;                // the live rows of Y, row k' at Bc + k' * N elements (kept blocks only)
 };
 
 template <typename T> __device__ __forceinline__ uint32_t f32_bits(T v);
@@ -79,7 +87,13 @@ __device__ __forceinline__ uint32_t mbcnt64(uint64_t m)
 // ---- A side: one workgroup = one block of 64 rows x 128 columns ------------------------------
 // Wave w scans rows 8w..8w+7, one 64-column word per load.  Lane 2j+h of the wave ends up
 // holding the bitmap word (row j, half h); entries are appended in (row, column) order.
-template <typename T, int PRED>
+// MODE A_FULL: bitmap words, column-any words and the block's list, all over the original k.
+// MODE A_MAPS: bitmap and column-any words only (row-compacted mode: the lists are made by A_LISTS).
+// MODE A_LISTS: the block is 64 rows x 128 *live* k (k' = 128 bj ..): its elements are gathered through
+//   kmap; it writes the list and the column-any words over k'.
+enum { A_FULL = 0, A_MAPS = 1, A_LISTS = 2 };
+
+template <typename T, int PRED, int MODE>
 __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lane, int wave, uint64_t *red,
                                        uint32_t *tot)
 {
@@ -88,18 +102,39 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
     const int64_t rbase = bi * MMM_AB_ROWS + wave * A_ROWS_PER_WAVE;
     const int64_t w_lo = k_lo / 64;
     const T *X = static_cast<const T *>(p.X);
+    const int64_t klim = MODE == A_LISTS ? (int64_t)*p.kinfo : p.K;   // number of (live) k
+    if (MODE == A_LISTS && k_lo >= klim) return;                      // no live k left for this block (whole workgroup)
     // keep words of the wave's 16 (row, half) pairs, one per lane 2j+h, requested together with X
     uint64_t kw = ~0ull;
-    if (p.keep_a != nullptr && lane < 2 * A_ROWS_PER_WAVE && rbase + (lane >> 1) < p.M && w_lo + (lane & 1) < p.WA)
+    if (MODE != A_LISTS && p.keep_a != nullptr && lane < 2 * A_ROWS_PER_WAVE && rbase + (lane >> 1) < p.M &&
+        w_lo + (lane & 1) < p.WA)
         kw = p.keep_a[(rbase + (lane >> 1)) * p.WA + w_lo + (lane & 1)];
+    int64_t korig[A_WORDS];   // A_LISTS: the original k of this lane's two columns
+#pragma unroll
+    for (int h = 0; h < A_WORDS; ++h) {
+        const int64_t k = k_lo + 64 * h + lane;
+        korig[h] = k;
+        if (MODE == A_LISTS) korig[h] = k < klim ? (int64_t)p.kmap[k] : -1;
+    }
     uint32_t u[A_ROWS_PER_WAVE][A_WORDS];
+    uint32_t kbit[A_ROWS_PER_WAVE] = {};   // A_LISTS: keep bits of this lane's elements, bit h of entry j
 #pragma unroll
     for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
 #pragma unroll
         for (int h = 0; h < A_WORDS; ++h) {
             const int64_t r = rbase + j, k = k_lo + 64 * h + lane;
             u[j][h] = 0;
-            if (r < p.M && k < p.K) u[j][h] = f32_bits<T>(X[r * p.ldx + k]);
+            if (MODE == A_LISTS) {
+                if (r < p.M && korig[h] >= 0) {
+                    u[j][h] = f32_bits<T>(X[r * p.ldx + korig[h]]);
+                    uint32_t bit = 1;
+                    if (p.keep_a != nullptr)
+                        bit = (uint32_t)(reinterpret_cast<const uint8_t *>(p.keep_a)[(r * p.WA) * 8 + (korig[h] >> 3)] >> (korig[h] & 7)) & 1u;
+                    kbit[j] |= bit << h;
+                }
+            } else if (r < p.M && k < p.K) {
+                u[j][h] = f32_bits<T>(X[r * p.ldx + k]);
+            }
         }
     }
     uint64_t colany[A_WORDS] = {0, 0};
@@ -108,9 +143,14 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
     for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
 #pragma unroll
         for (int h = 0; h < A_WORDS; ++h) {
-            uint64_t m = ballot64(keep_element<PRED>(u[j][h], p.thr_bits));   // lanes past K or M hold +0
-            m &= ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(kw >> 32), 2 * j + h) << 32) |
-                 (uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)kw, 2 * j + h);
+            uint64_t m;
+            if (MODE == A_LISTS) {
+                m = ballot64(keep_element<PRED>(u[j][h], p.thr_bits) && ((kbit[j] >> h) & 1u));
+            } else {
+                m = ballot64(keep_element<PRED>(u[j][h], p.thr_bits));   // lanes past K or M hold +0
+                m &= ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(kw >> 32), 2 * j + h) << 32) |
+                     (uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)kw, 2 * j + h);
+            }
             colany[h] |= m;
             const bool owner = __builtin_amdgcn_inverse_ballot_w64(1ull << (2 * j + h));   // lane 2j+h, as a constant mask
             mine_lo = owner ? (uint32_t)m : mine_lo;
@@ -120,7 +160,7 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
     const uint64_t mine = ((uint64_t)mine_hi << 32) | mine_lo;
     // bitmap words and per-wave entry offsets
     const bool have_word = lane < 2 * A_ROWS_PER_WAVE && rbase + (lane >> 1) < p.M && w_lo + (lane & 1) < p.WA;
-    if (have_word) p.a_bits[(rbase + (lane >> 1)) * p.WA + w_lo + (lane & 1)] = mine;
+    if (MODE != A_LISTS && have_word) p.a_bits[(rbase + (lane >> 1)) * p.WA + w_lo + (lane & 1)] = mine;
     const uint32_t my_cnt = (uint32_t)__popcll(mine);   // lanes past the wave's words hold 0
     uint32_t incl = my_cnt;
 #pragma unroll
@@ -139,7 +179,7 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
     for (int w = 0; w < wave; ++w) base += tot[w];
     uint32_t total = 0;
     for (int w = 0; w < BUILD_WAVES; ++w) total += tot[w];
-    if (threadIdx.x == 0) p.a_cnt[b] = total;
+    if (MODE != A_MAPS && threadIdx.x == 0) p.a_cnt[b] = total;
     if (threadIdx.x < 2 * A_WORDS) {   // column-any words of the two 32-row tiles of this block
         const int t = threadIdx.x >> 1, h = threadIdx.x & 1;
         const int64_t tile = bi * (MMM_AB_ROWS / MMM_COLANY_ROWS) + t;
@@ -147,9 +187,10 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
         {
             uint64_t any = 0;   // waves t*W/2 .. (t+1)*W/2-1 cover the 32 rows of tile t
             for (int w = t * (BUILD_WAVES / 2); w < (t + 1) * (BUILD_WAVES / 2); ++w) any |= red[w * A_WORDS + h];
-            p.a_colany[tile * p.WA + w_lo + h] = any;
+            (MODE == A_LISTS ? p.a_colany_c : p.a_colany)[tile * p.WA + w_lo + h] = any;
         }
     }
+    if (MODE == A_MAPS) return;
     // compacted entries {byte offset inside the multiplier's LDS slab, value}, in (row, column) order
     uint2 *ent = p.a_ent + (size_t)b * MMM_AB_CAP;
 #pragma unroll
@@ -175,7 +216,15 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
 }
 
 // ---- B side: one workgroup = 16 rows (values of k) x 64 blocks -------------------------------
-template <typename T, int BW>
+template <typename T> __device__ __forceinline__ T raw_zero();
+template <> __device__ __forceinline__ float raw_zero<float>() { return 0.f; }
+template <> __device__ __forceinline__ uint16_t raw_zero<uint16_t>() { return 0; }
+template <> __device__ __forceinline__ _Float16 raw_zero<_Float16>() { return (_Float16)0; }
+
+// COMPACT (row-compacted mode): the workgroup's 16 rows are the live rows k' = 16 piece ..; they are read
+// through kmap, their kept blocks are copied to row k' of Bc, and the transposed map over k' is written
+// instead of b_bits and the transposed map over k (which the plain workgroups write).
+template <typename T, int BW, bool COMPACT>
 __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int lane, int wave, uint32_t *pieces,
                                        uint8_t (*gpos)[B_ROWS_PER_WAVE][64], uint64_t (*gword)[B_ROWS_PER_WAVE])
 {
@@ -183,35 +232,47 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
     const int64_t piece = bb / p.WB, w = bb % p.WB;
     const int64_t kbase = piece * MMM_BT_PIECE + wave * B_ROWS_PER_WAVE;
     const T *Y = static_cast<const T *>(p.Y);
+    const int64_t klive = COMPACT ? (int64_t)*p.kinfo : 0;
+    // pieces past the last 128-step that holds a live k are never looked at (whole workgroup leaves)
+    if (COMPACT && piece * MMM_BT_PIECE >= (klive + MMM_AB_COLS - 1) / MMM_AB_COLS * MMM_AB_COLS) return;
     const int64_t nb_left = p.NB - w * 64;
     const uint64_t valid = nb_left >= 64 ? ~0ull : ((1ull << nb_left) - 1ull);
     uint32_t piece_bits = 0;
     // which blocks of the wave's rows the keep bitmaps leave switched on: lane r fetches the two
     // keep words of row r, so that all of them are in flight together
     uint64_t krw = ~0ull, kbw = ~0ull;
+    int64_t krow = -1;   // lane r: the row of Y behind the wave's row r (-1: none)
     {
         const int64_t kl = kbase + lane;
-        const bool mine = lane < B_ROWS_PER_WAVE && kl < p.K;
-        if (p.keep_rows != nullptr && mine) krw = p.keep_rows[kl >> 6];
-        if (p.keep_blocks != nullptr && mine) kbw = p.keep_blocks[kl * p.WB + w];
+        if (lane < B_ROWS_PER_WAVE) krow = COMPACT ? (kl < klive ? (int64_t)p.kmap[kl] : -1) : (kl < p.K ? kl : -1);
+        const bool mine = krow >= 0;
+        if (p.keep_rows != nullptr && mine) krw = p.keep_rows[krow >> 6];
+        if (p.keep_blocks != nullptr && mine) kbw = p.keep_blocks[krow * p.WB + w];
     }
     uint64_t kept[B_ROWS_PER_WAVE];
+    int64_t korig[B_ROWS_PER_WAVE];
 #pragma unroll
     for (int r = 0; r < B_ROWS_PER_WAVE; ++r) {
-        const int64_t k = kbase + r;
+        korig[r] = ((int64_t)__builtin_amdgcn_readlane((int32_t)(krow >> 32), r) << 32) |
+                   (int64_t)(uint32_t)__builtin_amdgcn_readlane((int32_t)krow, r);
+    }
+#pragma unroll
+    for (int r = 0; r < B_ROWS_PER_WAVE; ++r) {
+        const int64_t k = korig[r];
         const uint64_t kr = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(krw >> 32), r) << 32) |
                             (uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)krw, r);
         const uint64_t kb = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)(kbw >> 32), r) << 32) |
                             (uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)kbw, r);
-        kept[r] = k < p.K ? valid & kb & (0ull - ((kr >> (k & 63)) & 1ull)) : 0ull;
+        kept[r] = k >= 0 ? valid & kb & (0ull - ((kr >> (k & 63)) & 1ull)) : 0ull;
     }
     constexpr int PER = BW <= 16 ? BW : 16;   // loads in flight per lane and row
 #pragma unroll
     for (int r = 0; r < B_ROWS_PER_WAVE; ++r) {
-        const int64_t k = kbase + r;
+        const int64_t k = korig[r];
         uint64_t word = 0;
         if (kept[r] != 0) {
             const T *row = Y + k * p.ldy + w * 64 * BW;
+            T *crow = COMPACT ? static_cast<T *>(p.Bc) + (kbase + r) * p.N + w * 64 * BW : nullptr;
             const uint64_t bwmask = BW == 32 ? 0xffffffffull : ((1ull << BW) - 1ull);
             constexpr int ROUNDS = 4;   // gather path: at most ROUNDS loads of BPL kept blocks each
             const int nkept = __popcll(kept[r]);
@@ -232,7 +293,11 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
                     const int j = t * BPL + slot;
                     pos[t] = j < nkept ? (int)plist[j] : -1;
                     u[t] = 0;
-                    if (pos[t] >= 0) u[t] = f32_bits<T>(row[pos[t] * BW + lane % BW]);
+                    if (pos[t] >= 0) {
+                        const T v = row[pos[t] * BW + lane % BW];
+                        u[t] = f32_bits<T>(v);
+                        if (COMPACT) crow[pos[t] * BW + lane % BW] = v;
+                    }
                 }
 #pragma unroll
                 for (int t = 0; t < ROUNDS; ++t) {
@@ -251,7 +316,11 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
                     for (int j = 0; j < PER; ++j) {
                         const int blk = (j0 + j) * BPL + lane / BW;   // block (inside this word) of this lane's element
                         u[j] = 0;
-                        if ((kept[r] >> blk) & 1ull) u[j] = f32_bits<T>(row[(j0 + j) * 64 + lane]);
+                        if ((kept[r] >> blk) & 1ull) {
+                            const T v = row[(j0 + j) * 64 + lane];
+                            u[j] = f32_bits<T>(v);
+                            if (COMPACT) crow[(j0 + j) * 64 + lane] = v;
+                        }
                     }
 #pragma unroll
                     for (int j = 0; j < PER; ++j) {
@@ -262,7 +331,7 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
                 word = ballot64(((mine >> ((lane % BPL) * BW)) & bwmask) != 0);
             }
         }
-        if (k < p.K && lane == 0) p.b_bits[k * p.WB + w] = word;
+        if (!COMPACT && k >= 0 && lane == 0) p.b_bits[k * p.WB + w] = word;
         piece_bits |= (uint32_t)((word >> lane) & 1ull) << (wave * B_ROWS_PER_WAVE + r);
     }
     pieces[wave * 64 + lane] = piece_bits;
@@ -271,7 +340,7 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
         uint32_t v = 0;
         for (int w = 0; w < BUILD_WAVES; ++w) v |= pieces[w * 64 + lane];
         const int64_t blk = w * 64 + lane;
-        if (blk < p.NB) p.bt_pieces[blk * (p.WA * (64 / MMM_BT_PIECE)) + piece] = (uint16_t)v;
+        if (blk < p.NB) (COMPACT ? p.btc_pieces : p.bt_pieces)[blk * (p.WA * (64 / MMM_BT_PIECE)) + piece] = (uint16_t)v;
     }
 }
 
@@ -286,22 +355,88 @@ __global__ __launch_bounds__(BUILD_THREADS) void mmm_build_kernel(const BuildPar
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t b = blockIdx.x;
-    if (b < p.n_a) {
-        if (p.pred == MMM_PRED_NONZERO)
-            scan_a<T, MMM_PRED_NONZERO>(p, b, lane, wave, red, tot);
-        else if (p.pred == MMM_PRED_GT)
-            scan_a<T, MMM_PRED_GT>(p, b, lane, wave, red, tot);
-        else
-            scan_a<T, MMM_PRED_ABS_GT>(p, b, lane, wave, red, tot);
+    // workgroup ranges: [blocks of A over k | blocks of A over the live k | rows of Y | live rows of Y]
+    if (b < p.n_a + p.n_ac) {
+        const bool lists = b >= p.n_a;   // row-compacted mode: the second range makes the lists
+        const uint32_t ba = lists ? b - p.n_a : b;
+        if (p.n_ac == 0) {
+            if (p.pred == MMM_PRED_NONZERO)
+                scan_a<T, MMM_PRED_NONZERO, A_FULL>(p, ba, lane, wave, red, tot);
+            else if (p.pred == MMM_PRED_GT)
+                scan_a<T, MMM_PRED_GT, A_FULL>(p, ba, lane, wave, red, tot);
+            else
+                scan_a<T, MMM_PRED_ABS_GT, A_FULL>(p, ba, lane, wave, red, tot);
+        } else if (!lists) {
+            if (p.pred == MMM_PRED_NONZERO)
+                scan_a<T, MMM_PRED_NONZERO, A_MAPS>(p, ba, lane, wave, red, tot);
+            else if (p.pred == MMM_PRED_GT)
+                scan_a<T, MMM_PRED_GT, A_MAPS>(p, ba, lane, wave, red, tot);
+            else
+                scan_a<T, MMM_PRED_ABS_GT, A_MAPS>(p, ba, lane, wave, red, tot);
+        } else {
+            if (p.pred == MMM_PRED_NONZERO)
+                scan_a<T, MMM_PRED_NONZERO, A_LISTS>(p, ba, lane, wave, red, tot);
+            else if (p.pred == MMM_PRED_GT)
+                scan_a<T, MMM_PRED_GT, A_LISTS>(p, ba, lane, wave, red, tot);
+            else
+                scan_a<T, MMM_PRED_ABS_GT, A_LISTS>(p, ba, lane, wave, red, tot);
+        }
     } else {
+        const uint32_t bb = b - p.n_a - p.n_ac;
         const int64_t bw = p.N / p.NB;
-        if (bw == 8)
-            scan_b<T, 8>(p, b - p.n_a, lane, wave, pieces, gpos, gword);
-        else if (bw == 16)
-            scan_b<T, 16>(p, b - p.n_a, lane, wave, pieces, gpos, gword);
-        else
-            scan_b<T, 32>(p, b - p.n_a, lane, wave, pieces, gpos, gword);
+        if (bb < p.n_b) {
+            if (bw == 8)
+                scan_b<T, 8, false>(p, bb, lane, wave, pieces, gpos, gword);
+            else if (bw == 16)
+                scan_b<T, 16, false>(p, bb, lane, wave, pieces, gpos, gword);
+            else
+                scan_b<T, 32, false>(p, bb, lane, wave, pieces, gpos, gword);
+        } else {
+            if (bw == 8)
+                scan_b<T, 8, true>(p, bb - p.n_b, lane, wave, pieces, gpos, gword);
+            else if (bw == 16)
+                scan_b<T, 16, true>(p, bb - p.n_b, lane, wave, pieces, gpos, gword);
+            else
+                scan_b<T, 32, true>(p, bb - p.n_b, lane, wave, pieces, gpos, gword);
+        }
     }
+}
+
+// Row-compacted mode: number the rows of B that keep_rows leaves on.  One workgroup: every thread
+// counts a contiguous run of map words, a prefix sum over the threads places the runs, and every
+// thread then writes out the positions of its own bits:  kmap[k'] = k.  kinfo[0] = number of live k.
+__global__ __launch_bounds__(1024) void mmm_kmap_kernel(const uint64_t *keep_rows, int64_t K, int64_t WA, uint32_t *kinfo,
+                                                        uint32_t *kmap)
+{
+    __shared__ uint32_t sums[1024];
+    const int t = threadIdx.x;
+    const int64_t per = (WA + 1023) / 1024;
+    const int64_t w0 = (int64_t)t * per, w1 = min(WA, w0 + per);
+    auto word = [&](int64_t w) -> uint64_t {
+        uint64_t m = keep_rows[w];
+        const int64_t left = K - w * 64;   // bits past K do not count
+        if (left < 64) m &= (1ull << left) - 1ull;
+        return m;
+    };
+    uint32_t cnt = 0;
+    for (int64_t w = w0; w < w1; ++w) cnt += (uint32_t)__popcll(word(w));
+    sums[t] = cnt;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {   // inclusive prefix sum in LDS
+        const uint32_t o = t >= d ? sums[t - d] : 0u;
+        __syncthreads();
+        sums[t] += o;
+        __syncthreads();
+    }
+    uint32_t pos = sums[t] - cnt;
+    for (int64_t w = w0; w < w1; ++w) {
+        uint64_t m = word(w);
+        while (m != 0) {
+            kmap[pos++] = (uint32_t)(w * 64 + __builtin_ctzll(m));
+            m &= m - 1;
+        }
+    }
+    if (t == 1023) kinfo[0] = sums[1023];
 }
 
 // ---- statistics (off the hot path) -----------------------------------------------------------
@@ -387,11 +522,26 @@ hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStrea
     p.KBA = m->KBA;
     p.pred = a.pred;
     p.thr_bits = threshold_key(a.pred, a.threshold);
+    p.kinfo = m->kinfo;
+    p.kmap = m->kmap;
+    p.a_colany_c = m->a_colany_c;
+    p.btc_pieces = reinterpret_cast<uint16_t *>(m->btc_bits);
+    p.Bc = m->Bc;
     const int64_t n_a = a.X ? m->MBA * m->KBA : 0;
+    const int64_t n_ac = a.X && a.a_compact ? n_a : 0;
     const int64_t n_b = a.Y ? (m->WA * (64 / MMM_BT_PIECE)) * m->WB : 0;
-    if (n_a + n_b <= 0 || n_a + n_b > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int64_t n_bc = a.Y && a.b_compact ? n_b : 0;
+    const int64_t n_all = n_a + n_ac + n_b + n_bc;
+    if (n_all <= 0 || n_all > 0x7fffffffLL) return hipErrorInvalidValue;
     p.n_a = (uint32_t)n_a;
-    const dim3 grid((uint32_t)(n_a + n_b)), block(BUILD_THREADS);
+    p.n_ac = (uint32_t)n_ac;
+    p.n_b = (uint32_t)n_b;
+    const dim3 grid((uint32_t)n_all), block(BUILD_THREADS);
+    (void)hipGetLastError();   // drop any stale error another library left on this thread
+    if (a.Y && a.b_compact) {   // number the live rows first: the scans below read the numbering
+        hipLaunchKernelGGL(mmm_kmap_kernel, dim3(1), dim3(1024), 0, s, a.keep_rows, m->K, m->WA, m->kinfo, m->kmap);
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    }
     (void)hipGetLastError();   // drop any stale error another library left on this thread
     if (a.dtype == MMM_BF16)
         hipLaunchKernelGGL(mmm_build_kernel<uint16_t>, grid, block, 0, s, p);

@@ -46,12 +46,21 @@ struct mmm_maps {
     uint64_t *b_bits;
     uint64_t *bt_bits;
     uint64_t *stats;   // 4 words
+    // Row-compacted mode (B side built with keep_rows): k' numbers the rows keep_rows leaves on, and the
+    // matrix kernel walks k' instead of k.
+    uint32_t *kinfo;       // [0] = number of live k (device)
+    uint32_t *kmap;        // [K]: k' -> k
+    uint64_t *a_colany_c;  // [MT][WA]: column-any words of A over k'
+    uint64_t *btc_bits;    // [NB][WA]: the B map transposed, over k'
+    void *Bc;              // [K][N] elements: the kept blocks of live row k' of Y at row k'
     float *partials;   // split-K partial sums
     size_t partial_bytes;
     void *ws;
     size_t ws_bytes;
     // state
     bool a_built, b_built;
+    bool b_compact;   // the B side was built in row-compacted mode
+    bool a_compact;   // the lists of A were built over k' (for the numbering of the current B side)
     int32_t a_dtype, b_dtype;
     const void *a_src;   // address and leading dimension of the X the A side was built from (identity only)
     int64_t a_src_ld;
@@ -75,6 +84,8 @@ struct mmm_build_args {
     const uint64_t *keep_rows;
     const uint64_t *keep_blocks;
     int32_t dtype;
+    bool a_compact;   // list the blocks of A over the live k (the numbering exists or is made in this call)
+    bool b_compact;   // number the live rows (keep_rows given) and write the compacted B side too
 };
 
 struct mmm_plan {

@@ -62,6 +62,7 @@ struct MatmulParams {
     const uint64_t *a_colany;
     const uint64_t *b_bits;
     const uint64_t *bt_bits;
+    const uint32_t *kinfo;   // row-compacted mode: [0] = number of live k (the maps, lists and Y above are then over k'); else null
     int64_t M, K, N, NB, WA, WB, MT, KBA;
     int32_t bw;
     int32_t tiles_m, tiles_n, split_k, chunks_total, chunks_per_split;
@@ -152,8 +153,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     const int split = (int)((L / (uint32_t)p.tiles_n) % (uint32_t)p.split_k);
     const int tile_m = (int)(L / ((uint32_t)p.tiles_n * (uint32_t)p.split_k));
     const int64_t row0 = (int64_t)tile_m * TM;
-    const int chunk_begin = split * p.chunks_per_split;
-    const int chunk_end = min(chunk_begin + p.chunks_per_split, p.chunks_total);
+    // steps of this workgroup; in row-compacted mode only the steps that hold a live k exist, shared out anew
+    int chunks_live = p.chunks_total, per_split = p.chunks_per_split;
+    if (p.kinfo != nullptr) {
+        chunks_live = (int)(((int64_t)*p.kinfo + KC - 1) / KC);
+        per_split = (chunks_live + p.split_k - 1) / p.split_k;
+    }
+    const int chunk_begin = min(split * per_split, chunks_live);
+    const int chunk_end = min(chunk_begin + per_split, chunks_live);
     const uint32_t ldyb = (uint32_t)p.ldy * ESZ;   // bytes per row of Y (below 2^24: the host checks)
 
     floatx4 acc[GW][RT];
@@ -322,8 +329,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
     auto load_b = [&](const char *Yst, int64_t k0, uint32_t kb, int g) __attribute__((always_inline)) -> float {
         float v = to_f32<T>(*reinterpret_cast<const T *>(Yst + (__umul24(kb, ldyb) + coffb[g])));
         if (BW8) {   // a group spans two blocks: take only this lane's own block
-            const int64_t blk = (wcolb + coffb[g] / ESZ) >> 3;
-            if (!((p.b_bits[(k0 + kb) * p.WB + (blk >> 6)] >> (blk & 63)) & 1ull)) v = 0.f;
+            const int64_t blk = (wcolb + coffb[g] / ESZ) >> 3, kk = k0 + kb;
+            if (!((p.bt_bits[blk * p.WA + (kk >> 6)] >> (kk & 63)) & 1ull)) v = 0.f;
         }
         return v;
     };
@@ -640,6 +647,13 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtyp
     p.a_colany = m->a_colany;
     p.b_bits = m->b_bits;
     p.bt_bits = m->bt_bits;
+    if (m->b_compact) {   // everything the kernel walks is over the live rows k'
+        p.Y = m->Bc;
+        p.ldy = m->N;
+        p.a_colany = m->a_colany_c;
+        p.bt_bits = m->btc_bits;
+        p.kinfo = m->kinfo;
+    }
     p.M = m->M;
     p.K = m->K;
     p.N = m->N;

@@ -122,6 +122,23 @@ class MaskedMatmul:
         _, b, kw = B.mmm_maps_view_derived(self.maps)
         return self._bits_tensor(b, self.N // self.bw, kw)
 
+    def compacted(self):
+        """None unless the B side was built with keep_rows; else (live_count int32 [1], kmap int32 [K], a_colany_c int64
+        [ceil(M/32), ceil(K/64)], btc_bits int64 [NB, ceil(K/64)]) as views of the workspace."""
+        on, kc, km, ca, bt = B.mmm_maps_view_compacted(self.maps)
+        if not on:
+            return None
+        base = self.workspace.data_ptr()
+        wa = (self.K + 63) // 64
+
+        def view(addr, nbytes, dt):
+            assert 0 <= addr - base and addr - base + nbytes <= self.workspace.numel()
+            return self.workspace[addr - base: addr - base + nbytes].view(dt)
+
+        return (view(kc, 4, torch.int32), view(km, self.K * 4, torch.int32),
+                view(ca, ((self.M + 31) // 32) * wa * 8, torch.int64).view(-1, wa),
+                view(bt, (self.N // self.bw) * wa * 8, torch.int64).view(-1, wa))
+
     def a_lists(self):
         """(counts int32 [blocks_m, blocks_k], entries int64 [blocks_m * blocks_k, capacity]) as views of the workspace."""
         c, e, bm, bk, cap = B.mmm_maps_view_lists(self.maps)

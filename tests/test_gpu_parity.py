@@ -42,16 +42,28 @@ def derived_from_bits(ab, bb, M, K, NB):
     return colany, bt
 
 
+def live_rows(w):
+    """The k that keep_rows leaves on (row-compacted mode numbers them k' = 0, 1, ...), or None without keep_rows."""
+    if w.keep_rows is None:
+        return None
+    return np.nonzero(synth.unpack_bits(w.keep_rows.reshape(1, -1), w.K)[0])[0]
+
+
 def check_lists(run, ab, w, what):
     """The blocked non-zero lists of A against the oracle's bitmap and the input values: per 64 x 128 block the
-    same set of {slab offset, value bits} words (their order is the library's own), then the stated padding."""
+    same set of {slab offset, value bits} words (their order is the library's own), then the stated padding.  With
+    keep_rows the blocks are over the live columns only."""
     counts, ents = run.lists_host()
     keep = synth.unpack_bits(ab, w.K)
     xbits = np.ascontiguousarray(w.X, dtype=np.float32).view(np.uint32)
+    live = live_rows(w)
+    if live is not None:
+        keep, xbits = keep[:, live], xbits[:, live]
+    kcols = keep.shape[1]
     MB, KB = (w.M + 63) // 64, (w.K + 127) // 128
     assert counts.shape == (MB, KB), what
     for bm in range(MB):
-        for bk in range(KB):
+        for bk in range((kcols + 127) // 128):
             kp = keep[bm * 64:(bm + 1) * 64, bk * 128:(bk + 1) * 128]
             r, c = np.nonzero(kp)
             want = (xbits[bm * 64 + r, bk * 128 + c].astype(np.uint64) << np.uint64(32)) | (272 * c + 16 * (r % 16) + 4 * (r // 16)).astype(np.uint64)
@@ -60,6 +72,32 @@ def check_lists(run, ab, w, what):
             assert n == len(want), f"{what}: block ({bm},{bk}) count {n} want {len(want)}"
             np.testing.assert_array_equal(np.sort(got[:n]), np.sort(want), err_msg=f"{what}: block ({bm},{bk}) entries")
             assert (got[n:] == np.uint64(34816)).all(), f"{what}: block ({bm},{bk}) padding"
+
+
+def check_compacted(run, ab, bb, w, what):
+    """Row-compacted mode: the numbering of the live rows and the maps over it, against copies derived from the
+    oracle's bitmaps and the keep_rows input."""
+    comp = run.eng.compacted()
+    live = live_rows(w)
+    if live is None:
+        assert comp is None, what
+        return
+    assert comp is not None, what
+    torch.cuda.synchronize()
+    count, kmap, colany_c, btc = (t.cpu().numpy() for t in comp)
+    assert int(count[0]) == len(live), what
+    np.testing.assert_array_equal(kmap[: len(live)], live, err_msg=f"{what}: kmap")
+    words = (len(live) + 127) // 128 * 2          # the words the multiplication looks at
+    if words == 0:
+        return
+    a = synth.unpack_bits(ab, w.K)[:, live]
+    pad = (-w.M) % 32
+    a = np.concatenate([a, np.zeros((pad, len(live)), bool)]) if pad else a
+    exp_c = synth.pack_bits(np.pad(a.reshape(-1, 32, len(live)).any(axis=1), ((0, 0), (0, words * 64 - len(live)))))
+    exp_b = synth.pack_bits(np.pad(synth.unpack_bits(bb, w.N // w.bw)[live].T, ((0, 0), (0, words * 64 - len(live)))))
+    have = min(words, (w.K + 63) // 64)          # a short K has fewer words than a whole step
+    np.testing.assert_array_equal(colany_c.view(np.uint64)[:, :have], exp_c[:, :have], err_msg=f"{what}: a_colany over k'")
+    np.testing.assert_array_equal(btc.view(np.uint64)[:, :have], exp_b[:, :have], err_msg=f"{what}: bt_bits over k'")
 
 
 def check_workload(w, what, exact=False, **ld):
@@ -73,6 +111,7 @@ def check_workload(w, what, exact=False, **ld):
     exp_colany, exp_bt = derived_from_bits(ab, bb, w.M, w.K, w.N // w.bw)
     np.testing.assert_array_equal(colany, exp_colany, err_msg=f"{what}: a_colany")
     np.testing.assert_array_equal(bt, exp_bt, err_msg=f"{what}: bt_bits")
+    check_compacted(run, ab, bb, w, what)
     if w.M * w.K <= 1 << 22:
         check_lists(run, ab, w, what)
     assert run.eng.stats() == oracle.counts(ab, bb, w.M, w.K, w.N, w.bw), what
@@ -221,6 +260,33 @@ def test_non_finite_value_inside_an_occupied_block(bw, path):
     assert not np.isfinite(C[hit, j]).any()
     rest = C[~hit, j]
     assert np.all(np.isnan(rest) | (rest == C_ref[~hit, j]))
+
+
+def test_rebuilding_a_row_compacted_b_side_alone_leaves_a_unbuilt():
+    mm.mmm_set_option("matmul_path", mm.MMM_PATH_MATRIX)
+    w = synth.random_masked(70, 400, 96, 16, 0.3, 0.5, 61, dist="smallint", p_rows=0.3)
+    _, _, C_ref, _ = oracle.run_workload(w)
+    run = HipRun(w)
+    run.build()
+    run.build(a=False, b=True)             # the numbering of the live rows was made anew: the lists of A are void
+    with pytest.raises(mm.MmmError) as e:
+        run.matmul()
+    assert e.value.status == mm.binding.MMM_ERR_MAPS_MISMATCH
+    run.build(a=True, b=False)
+    run.matmul()
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(run.C.cpu().numpy(), C_ref)
+    # other rows switched on, B rebuilt together with A
+    w2 = synth.random_masked(70, 400, 96, 16, 0.3, 0.5, 62, dist="smallint", p_rows=0.6)
+    w2.X, w2.keep_a = w.X, w.keep_a
+    _, _, C2_ref, _ = oracle.run_workload(w2)
+    run.Y.copy_(torch.from_numpy(w2.Y))
+    run.keep_rows.copy_(torch.from_numpy(w2.keep_rows.view(np.int64)))
+    run.keep_blocks.copy_(torch.from_numpy(w2.keep_blocks.view(np.int64)))
+    run.build()
+    run.matmul()
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(run.C.cpu().numpy(), C2_ref)
 
 
 def test_matmul_refuses_another_x_than_the_one_built_from():
