@@ -30,6 +30,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3   # 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flops x 2.4 GHz
 FP32_MFMA_PEAK_TFLOPS = 157.3
+BF16_MFMA_PEAK_TFLOPS = 2500.0    # dense bf16 / fp16 matrix peak, published
 HEADLINE_POINT = 2                # index into the sweep: keep fraction 0.20 = 80 % zeros
 
 
@@ -234,13 +235,18 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
         + a_bits_b + colany_b + a_list_b + b_bits_b + bt_b
     matmul_bytes = a_list_b + occ_b * w.bw * esz + colany_b + bt_b + w.M * w.N * 4
 
+    # arithmetic peak the multiplication is priced against: fp32 inputs run on fp32 units (vector FMA and the fp32
+    # matrix instruction share one peak); 16-bit inputs on the matrix path run on the 16-bit matrix instructions
+    mfma16 = w.dtype != synth.DT_F32 and path == mm.MMM_PATH_MATRIX
+    arith_peak, arith_name = (BF16_MFMA_PEAK_TFLOPS, "mfma") if mfma16 else (FP32_VECTOR_PEAK_TFLOPS, "alu")
+
     def floors(nbytes, flops, t_ms):
         """Roofline of one kernel: the floor is the larger of the time its algorithmic bytes need at the HBM peak
-        and the time its useful flops need at the fp32 vector peak."""
+        and the time its useful flops need at the arithmetic peak."""
         t_hbm = nbytes / (HBM_PEAK_GBS * 1e9) * 1e6
-        t_alu = flops / (FP32_VECTOR_PEAK_TFLOPS * 1e12) * 1e6
+        t_alu = flops / (arith_peak * 1e12) * 1e6
         t_us = t_ms * 1e3
-        bound = "alu" if t_alu > t_hbm else "hbm"
+        bound = arith_name if t_alu > t_hbm else "hbm"
         r = {"avg_launch_us": t_us, "algorithmic_bytes": nbytes, "useful_flops": flops,
              "t_hbm_floor_us": t_hbm, "t_alu_floor_us": t_alu, "bound": bound,
              "frac_hbm": t_hbm / t_us, "frac_alu": t_alu / t_us, "frac": max(t_hbm, t_alu) / t_us,
@@ -250,12 +256,13 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
     rb = floors(build_bytes, 0.0, t_build)
     rm = floors(matmul_bytes, useful_flops, t_matmul)
     rm["issued_TFLOPs"] = issued_flops / (t_matmul * 1e-3) / 1e12
-    rm["issued_frac_of_fp32_peak"] = rm["issued_TFLOPs"] / FP32_MFMA_PEAK_TFLOPS
+    rm["issued_frac_of_arith_peak"] = rm["issued_TFLOPs"] / arith_peak
+    rm["arith_peak_TFLOPs"] = arith_peak
     rm["useful_over_issued"] = useful_flops / issued_flops if issued_flops else None
     mm_kernel = "mmm_matmul_kernel" if path == mm.MMM_PATH_MATRIX else "mmm_pairs_kernel"
     dom_name, dom = (mm_kernel, rm) if t_matmul >= t_build else ("mmm_build_kernel", rb)
-    if dom["bound"] == "alu":
-        roofline = {"bound": "alu", "achieved": dom["achieved_TFLOPs"], "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    if dom["bound"] != "hbm":
+        roofline = {"bound": dom["bound"], "achieved": dom["achieved_TFLOPs"], "peak": arith_peak, "unit": "TFLOP/s"}
     else:
         roofline = {"bound": "hbm", "achieved": dom["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     roofline.update({"frac": dom["frac"], "traffic": recorded_traffic(w.name, dom_name),

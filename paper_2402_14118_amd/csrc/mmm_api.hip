@@ -138,7 +138,8 @@ mmm_plan make_plan(const mmm_maps *m, int32_t dt)
 //     pairs  ~ 130 us + 24500 us * p_A * p_B      matrix ~ 95 us + 1000 us * p_B      (per 4096^3)
 // so for matrices of many rows the pair kernel is ahead iff p_B * (1 - 24.5 * p_A) > 0.035, which
 // needs p_A below 0.04; for matrices of at most 64 rows (one tile of the matrix kernel, mostly
-// empty, and a latency-bound launch) it is ahead up to p_A * p_B of about 0.02.  Densities are
+// empty, and a latency-bound launch) it is ahead up to p_A * p_B of about 0.02, and for small problems
+// (256^3) with short lists as well.  Densities are
 // known only after a mmm_maps_stats call (the counts of the most recent one are kept as the
 // estimate, also across rebuilds: emergent sparsity levels are stable from step to step); without
 // one the shape decides alone.
@@ -151,6 +152,10 @@ int32_t choose_path(const mmm_maps *m)
     const double p_a = known ? (double)m->stats_nnz_a / ((double)m->M * (double)m->K) : 0.0;
     const double p_b = known ? (double)m->stats_occ_b / ((double)m->K * (double)m->NB) : 0.0;
     if (m->M <= 64) return !known || p_a * p_b <= 0.02 ? MMM_PATH_PAIRS : MMM_PATH_MATRIX;
+    // small problems (the matrix kernel would fill less than half the machine) with short lists are bound by
+    // latency, of which the pair kernel has less
+    const int64_t tiles = ((m->M + 63) / 64) * ((m->N + 127) / 128);
+    if (known && tiles < 128 && p_a * p_b * (double)m->K <= 64.0) return MMM_PATH_PAIRS;
     return known && p_b * (1.0 - 24.5 * p_a) > 0.035 ? MMM_PATH_PAIRS : MMM_PATH_MATRIX;
 }
 
