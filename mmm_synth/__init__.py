@@ -29,6 +29,7 @@ PRED_ABS_GT = 2   # keep iff |x| > threshold
 DT_F32 = 0
 DT_BF16 = 1
 DT_F16 = 2
+DT_F64 = 3        # X, Y (and C) in double: X and Y of the workload are float64 arrays
 
 
 def pack_bits(flags: np.ndarray) -> np.ndarray:
@@ -116,7 +117,15 @@ class Workload:
         return self.N // self.bw
 
 
-def _values(rng: np.random.Generator, shape, dist: str, a: float, b: float) -> np.ndarray:
+def _values(rng: np.random.Generator, shape, dist: str, a: float, b: float, f64: bool = False) -> np.ndarray:
+    if f64:   # double-precision workloads draw doubles
+        if dist == "uniform":
+            return rng.uniform(a, b, size=shape)
+        if dist == "normal":
+            return rng.standard_normal(size=shape) * b + a
+        if dist == "smallint":
+            return rng.choice(np.array([-2.0, -1.0, 1.0, 2.0]), size=shape)
+        raise ValueError(dist)
     if dist == "uniform":
         return rng.uniform(a, b, size=shape).astype(np.float32)
     if dist == "normal":
@@ -139,8 +148,8 @@ def random_masked(M: int, K: int, N: int, bw: int, p_a: float, p_b: float, seed:
     keep = (u < p)."""
     assert N % bw == 0
     rng = np.random.Generator(np.random.PCG64(seed))
-    X = _values(rng, (M, K), dist, lo, hi)
-    Y = _values(rng, (K, N), dist, lo, hi)
+    X = _values(rng, (M, K), dist, lo, hi, dtype == DT_F64)
+    Y = _values(rng, (K, N), dist, lo, hi, dtype == DT_F64)
     ua = rng.random(size=(M, K), dtype=np.float32)
     keep_rows = None
     if p_rows is not None:

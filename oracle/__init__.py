@@ -48,6 +48,15 @@ def _f32(a) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.float32)
 
 
+def _is64(a) -> bool:
+    """Double-precision inputs take the *_f64 functions (same definitions, long double accumulation)."""
+    return isinstance(a, np.ndarray) and a.dtype == np.float64
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
 def _u64(a) -> Optional[np.ndarray]:
     return None if a is None else np.ascontiguousarray(a, dtype=np.uint64)
 
@@ -61,19 +70,21 @@ def set_threads(n: int) -> None:
 
 
 def a_bits(X, pred=PRED_NONZERO, threshold=0.0, keep_bits=None) -> np.ndarray:
-    X = _f32(X)
+    f64 = _is64(X)
+    X = _f64(X) if f64 else _f32(X)
     M, K = X.shape
     out = np.empty((M, (K + 63) // 64), dtype=np.uint64)
     kb = _u64(keep_bits)
     if kb is not None:
         assert kb.shape == out.shape
-    _L().oracle_a_bits(_p(X), ctypes.c_int64(M), ctypes.c_int64(K), ctypes.c_int64(K),
+    (_L().oracle_a_bits_f64 if f64 else _L().oracle_a_bits)(_p(X), ctypes.c_int64(M), ctypes.c_int64(K), ctypes.c_int64(K),
                        ctypes.c_int(pred), ctypes.c_float(threshold), _p(kb), _p(out))
     return out
 
 
 def b_bits(Y, bw: int, keep_rows=None, keep_blocks=None) -> np.ndarray:
-    Y = _f32(Y)
+    f64 = _is64(Y)
+    Y = _f64(Y) if f64 else _f32(Y)
     K, N = Y.shape
     assert N % bw == 0
     NB = N // bw
@@ -83,7 +94,7 @@ def b_bits(Y, bw: int, keep_rows=None, keep_blocks=None) -> np.ndarray:
         assert kr.size == (K + 63) // 64
     if kb is not None:
         assert kb.shape == out.shape
-    _L().oracle_b_bits(_p(Y), ctypes.c_int64(K), ctypes.c_int64(N), ctypes.c_int64(N),
+    (_L().oracle_b_bits_f64 if f64 else _L().oracle_b_bits)(_p(Y), ctypes.c_int64(K), ctypes.c_int64(N), ctypes.c_int64(N),
                        ctypes.c_int64(bw), _p(kr), _p(kb), _p(out))
     return out
 
@@ -117,22 +128,25 @@ def dense_ref(A, B) -> np.ndarray:
 
 
 def mmm(X, Y, abits, bbits, bw: int, C_in=None, want_mag: bool = True, rows=None):
-    """Returns (C fp32 [M,N], absAB fp64 [M,N] or None).  With C_in the product is
-    added to it (accumulate mode).  rows=(r0,r1) computes only those rows (the
-    others are left as C_in or zero)."""
-    X, Y = _f32(X), _f32(Y)
+    """Returns (C [M,N], absAB fp64 [M,N] or None); C is fp32, or fp64 for double inputs.  With C_in the product is
+    added to it (accumulate mode).  rows=(r0,r1) computes only those rows (the others are left as C_in or zero)."""
+    f64 = _is64(X)
+    assert f64 == _is64(Y)
+    X, Y = (_f64(X), _f64(Y)) if f64 else (_f32(X), _f32(Y))
+    ct = np.float64 if f64 else np.float32
     M, K = X.shape
     K2, N = Y.shape
     assert K == K2 and N % bw == 0
     acc = C_in is not None
-    C = np.array(C_in, dtype=np.float32, order="C", copy=True) if acc else np.zeros((M, N), np.float32)
+    C = np.array(C_in, dtype=ct, order="C", copy=True) if acc else np.zeros((M, N), ct)
     mag = np.zeros((M, N), dtype=np.float64) if want_mag else None
     r0, r1 = (0, M) if rows is None else rows
-    _L().oracle_mmm_rows(_p(X), ctypes.c_int64(K), _p(Y), ctypes.c_int64(N),
-                         _p(_u64(abits)), _p(_u64(bbits)),
-                         ctypes.c_int64(M), ctypes.c_int64(K), ctypes.c_int64(N), ctypes.c_int64(bw),
-                         ctypes.c_int64(r0), ctypes.c_int64(r1),
-                         _p(C), ctypes.c_int64(N), _p(mag), ctypes.c_int(1 if acc else 0))
+    (_L().oracle_mmm_rows_f64 if f64 else _L().oracle_mmm_rows)(
+        _p(X), ctypes.c_int64(K), _p(Y), ctypes.c_int64(N),
+        _p(_u64(abits)), _p(_u64(bbits)),
+        ctypes.c_int64(M), ctypes.c_int64(K), ctypes.c_int64(N), ctypes.c_int64(bw),
+        ctypes.c_int64(r0), ctypes.c_int64(r1),
+        _p(C), ctypes.c_int64(N), _p(mag), ctypes.c_int(1 if acc else 0))
     return C, mag
 
 

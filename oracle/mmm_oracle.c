@@ -25,6 +25,10 @@
  * MMM only skips products that are zero, so it reaches exactly the plain
  * result; the oracle therefore is the plain definition written out, with a
  * double-precision accumulator so that it spends none of the error budget.
+ * The paper also reports double-precision runs (section 4, table of the server
+ * machines: float and double); the *_f64 functions are the same definitions on
+ * double inputs, accumulated in long double (64-bit significand on x86) for
+ * the same reason.
  *
  * Readings taken where the paper is silent or at odds with itself:
  *   - bit = 1 means occupied / non-zero (text and caption; the pseudocode of
@@ -273,4 +277,99 @@ void oracle_counts(const uint64_t *a_bits, const uint64_t *b_bits,
     *nnz_a = na;
     *occ_b = nb;
     *useful_macs = macs;
+}
+
+/* ---- double-precision inputs (section 4, table of the server machines) ------------------------
+ * The same definitions as above with X, Y and C in double. */
+void oracle_a_bits_f64(const double *X, int64_t M, int64_t K, int64_t ldx, int pred, float threshold,
+                       const uint64_t *keep_bits, uint64_t *a_bits)
+{
+    const int64_t W = (K + 63) / 64;
+    memset(a_bits, 0, (size_t)(M * W) * sizeof(uint64_t));
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t k = 0; k < K; ++k) {
+            const double x = X[i * ldx + k];
+            int keep;
+            if (pred == ORACLE_PRED_GT)
+                keep = x > (double)threshold;
+            else if (pred == ORACLE_PRED_ABS_GT)
+                keep = fabs(x) > (double)threshold;
+            else
+                keep = 1;
+            if (keep_bits && !get_bit(keep_bits + i * W, k))
+                keep = 0;
+            if (keep && x != 0.0)
+                set_bit(a_bits + i * W, k);
+        }
+    }
+}
+
+void oracle_b_bits_f64(const double *Y, int64_t K, int64_t N, int64_t ldy, int64_t bw,
+                       const uint64_t *keep_rows, const uint64_t *keep_blocks, uint64_t *b_bits)
+{
+    const int64_t NB = N / bw;
+    const int64_t W = (NB + 63) / 64;
+    memset(b_bits, 0, (size_t)(K * W) * sizeof(uint64_t));
+    for (int64_t k = 0; k < K; ++k) {
+        if (keep_rows && !get_bit(keep_rows, k))
+            continue;
+        for (int64_t jb = 0; jb < NB; ++jb) {
+            if (keep_blocks && !get_bit(keep_blocks + k * W, jb))
+                continue;
+            int any = 0;
+            for (int64_t j = jb * bw; j < (jb + 1) * bw; ++j)
+                if (Y[k * ldy + j] != 0.0)
+                    any = 1;
+            if (any)
+                set_bit(b_bits + k * W, jb);
+        }
+    }
+}
+
+/* Fig. "skip computation when A is sparse" / Fig. "MMM Pseudocode" on doubles: i, k, j loops that
+ * skip zero A[i,k] and unoccupied blocks; one row of long double accumulators, one rounding to
+ * double at the end; absAB as above. */
+void oracle_mmm_rows_f64(const double *X, int64_t ldx, const double *Y, int64_t ldy,
+                         const uint64_t *a_bits, const uint64_t *b_bits,
+                         int64_t M, int64_t K, int64_t N, int64_t bw,
+                         int64_t row0, int64_t row1,
+                         double *C, int64_t ldc, double *absAB, int accumulate)
+{
+    const int64_t WA = (K + 63) / 64;
+    const int64_t NB = N / bw;
+    const int64_t WB = (NB + 63) / 64;
+    (void)M;
+#pragma omp parallel
+    {
+        long double *acc = (long double *)malloc((size_t)N * sizeof(long double));
+        long double *mag = (long double *)malloc((size_t)N * sizeof(long double));
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t i = row0; i < row1; ++i) {
+            for (int64_t j = 0; j < N; ++j) {
+                acc[j] = accumulate ? (long double)C[i * ldc + j] : 0.0L;
+                mag[j] = accumulate ? fabsl((long double)C[i * ldc + j]) : 0.0L;
+            }
+            for (int64_t k = 0; k < K; ++k) {
+                if (!get_bit(a_bits + i * WA, k))
+                    continue;
+                const long double a = (long double)X[i * ldx + k];
+                for (int64_t jb = 0; jb < NB; ++jb) {
+                    if (!get_bit(b_bits + k * WB, jb))
+                        continue;
+                    for (int64_t j = jb * bw; j < (jb + 1) * bw; ++j) {
+                        const long double b = (long double)Y[k * ldy + j];
+                        acc[j] += a * b;
+                        mag[j] += fabsl(a) * fabsl(b);
+                    }
+                }
+            }
+            for (int64_t j = 0; j < N; ++j) {
+                C[i * ldc + j] = (double)acc[j];
+                if (absAB)
+                    absAB[i * N + j] = (double)mag[j];
+            }
+        }
+        free(acc);
+        free(mag);
+    }
 }

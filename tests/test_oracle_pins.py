@@ -52,14 +52,14 @@ def np_product64(w):
 def brute_force_exact(w):
     """Pure-Python triple loop in exact rational arithmetic."""
     a_nz, b_occ = np_masks(w)
-    C = np.zeros((w.M, w.N), dtype=np.float32)
+    C = np.zeros((w.M, w.N), dtype=w.X.dtype)       # float32, or float64 for double-precision workloads
     for i in range(w.M):
         for j in range(w.N):
             s = Fraction(0)
             for k in range(w.K):
                 if a_nz[i, k] and b_occ[k, j // w.bw]:
                     s += Fraction(float(w.X[i, k])) * Fraction(float(w.Y[k, j]))
-            C[i, j] = np.float32(float(s))
+            C[i, j] = C.dtype.type(float(s))          # one rounding of the exact sum (float() rounds to nearest double)
     return C
 
 
@@ -81,6 +81,49 @@ def test_brute_force_tiny(M, K, N, bw):
         A = oracle.materialize_a(w.X, ab)
         B = oracle.materialize_b(w.Y, w.bw, bb)
         np.testing.assert_array_equal(C, oracle.dense_ref(A, B).astype(np.float32))
+
+
+# ---- double-precision inputs: the same pins on the *_f64 functions -----------------------------
+@pytest.mark.parametrize("M,K,N,bw", [(1, 1, 1, 1), (3, 5, 4, 2), (7, 16, 12, 4), (5, 70, 24, 3), (4, 130, 6, 6)])
+def test_brute_force_tiny_f64(M, K, N, bw):
+    """Exact rational sums rounded once to double: the long double accumulator may differ from that by its own
+    rounding of partial sums, which is below half an ulp of double times the number of terms / 2048."""
+    for seed, (pa, pb) in enumerate([(0.5, 0.5), (0.2, 0.7), (1.0, 1.0)]):
+        w = synth.random_masked(M, K, N, bw, pa, pb, 300 + seed, dtype=synth.DT_F64, p_rows=0.8 if seed % 2 else None)
+        assert w.X.dtype == np.float64 and w.Y.dtype == np.float64
+        ab, bb, C, mag = oracle.run_workload(w)
+        assert C.dtype == np.float64
+        a_nz, b_occ = np_masks(w)
+        np.testing.assert_array_equal(synth.unpack_bits(ab, w.K), a_nz)
+        np.testing.assert_array_equal(synth.unpack_bits(bb, w.N // w.bw), b_occ)
+        want = brute_force_exact(w)
+        assert np.all(np.abs(C - want) <= np.spacing(np.abs(want)) + 2.0 ** -60 * mag)
+        # integer inputs: exact
+        wi = synth.random_masked(M, K, N, bw, pa, pb, 400 + seed, dtype=synth.DT_F64, dist="smallint")
+        np.testing.assert_array_equal(oracle.run_workload(wi)[2], brute_force_exact(wi))
+
+
+def test_f64_all_keep_identity_and_tiny_values():
+    rng = np.random.default_rng(17)
+    X = rng.uniform(0.5, 1.5, size=(21, 50))
+    Y = rng.uniform(-1.5, -0.5, size=(50, 32))
+    C, mag = oracle.mmm(X, Y, oracle.a_bits(X), oracle.b_bits(Y, 8), 8)
+    ref = (X.astype(np.longdouble) @ Y.astype(np.longdouble))
+    assert np.all(np.abs(C.astype(np.longdouble) - ref) <= np.abs(ref) * 2.0 ** -52)
+    np.testing.assert_allclose(mag, np.abs(X) @ np.abs(Y), rtol=1e-14)
+    eye = np.eye(32)
+    kb = synth.pack_bits(rng.random((32, 4)) < 0.5)
+    Y2 = rng.standard_normal((32, 32))
+    C2, _ = oracle.mmm(eye, Y2, oracle.a_bits(eye), oracle.b_bits(Y2, 8, None, kb), 8)
+    np.testing.assert_array_equal(C2, np.where(np.repeat(synth.unpack_bits(kb, 4), 8, axis=1), Y2, 0))   # C = N(Y)
+    # values float cannot hold: 1e-310 (a double denormal) is non-zero, 1e300 passes > and |.| >
+    X3 = np.array([[0.0, -0.0, 1e-310, -1e300, 2.5e-320, np.nan]])
+    assert synth.unpack_bits(oracle.a_bits(X3), 6)[0].tolist() == [False, False, True, True, True, True]
+    assert synth.unpack_bits(oracle.a_bits(X3, synth.PRED_GT, 0.0), 6)[0].tolist() == [False, False, True, False, True, False]
+    assert synth.unpack_bits(oracle.a_bits(X3, synth.PRED_ABS_GT, 1.0), 6)[0].tolist() == [False, False, False, True, False, False]
+    Y3 = np.zeros((1, 16))
+    Y3[0, 9] = 4.9e-324
+    assert synth.unpack_bits(oracle.b_bits(Y3, 8), 2)[0].tolist() == [False, True]
 
 
 def test_all_keep_is_textbook_gemm():
