@@ -30,19 +30,28 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3   # 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flops x 2.4 GHz
 FP32_MFMA_PEAK_TFLOPS = 157.3
+FP64_VECTOR_PEAK_TFLOPS = 78.6    # published; the pair kernel's FMAs on double inputs
 BF16_MFMA_PEAK_TFLOPS = 2500.0    # dense bf16 / fp16 matrix peak, published
 HEADLINE_POINT = 2                # index into the sweep: keep fraction 0.20 = 80 % zeros
 
 
 def parse_workload(name):
     import mmm_synth as synth
-    if name.startswith("cfg3"):       # cfg3:<i> = diagonal point i of the sweep; cfg3:<ia>:<ib> = keep index of A, of B
+    if name.startswith("cfg3") and not name.startswith("cfg3_f64"):       # cfg3:<i> = diagonal point i of the sweep; cfg3:<ia>:<ib> = keep index of A, of B
         f = name.split(":")
         ia = int(f[1]) if len(f) > 1 else 3
         ib = int(f[2]) if len(f) > 2 else ia
         return synth.config(3, ia, ib)
     if name == "colsparse":   # beyond the five configurations: column-structured A, MLP down-projection shape
         return synth.column_sparse(2048, 16384, 4096, 32, 0.1, 1.0, 1.0, 2001)
+    if name == "cfg2_f64":    # double precision (the paper reports float and double): the shape and densities of cfg2
+        return synth.random_masked(2048, 2048, 2048, 16, 0.1, 0.1, 1002, "normal", 0.0, 1.0, name="cfg2_2048_p10_bw16_f64",
+                                   dtype=synth.DT_F64)
+    if name.startswith("cfg3_f64"):
+        ip = int(name.split(":")[1]) if ":" in name else 3
+        p = synth.SWEEP_P[ip]
+        return synth.random_masked(4096, 4096, 4096, 16, p, p, 3000 + 11 * ip, "uniform", -1.0, 1.0,
+                                   name=f"cfg3_4096_p{int(p*100):02d}_bw16_f64", dtype=synth.DT_F64)
     if name == "colsparse_bf16":
         return synth.column_sparse(2048, 16384, 4096, 32, 0.1, 1.0, 1.0, 2001, dtype=synth.DT_BF16)
     return synth.config(int(name[3:]))
@@ -75,19 +84,22 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
     import mmm_synth as synth
     import paper_2402_14118_amd as mm
 
-    esz = 4 if w.dtype == synth.DT_F32 else 2
+    esz = {synth.DT_F32: 4, synth.DT_F64: 8}.get(w.dtype, 2)
+    csz = 8 if w.dtype == synth.DT_F64 else 4
 
     def up(a):
         return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
-    if w.dtype != synth.DT_F32:
+    if w.dtype == synth.DT_F64:
+        X, Y = up(np.asarray(w.X, dtype=np.float64)), up(np.asarray(w.Y, dtype=np.float64))
+    elif w.dtype != synth.DT_F32:
         X, Y = up(w.X_bits.view(np.int16)), up(w.Y_bits.view(np.int16))
     else:
         X, Y = up(w.X), up(w.Y)
     keep_a = None if w.keep_a is None else up(w.keep_a.view(np.int64))
     keep_rows = None if w.keep_rows is None else up(w.keep_rows.view(np.int64))
     keep_blocks = None if w.keep_blocks is None else up(w.keep_blocks.view(np.int64))
-    C = torch.empty((w.M, w.N), dtype=torch.float32, device="cuda")
+    C = torch.empty((w.M, w.N), dtype=torch.float64 if w.dtype == synth.DT_F64 else torch.float32, device="cuda")
     eng = mm.MaskedMatmul(w.M, w.K, w.N, w.bw, w.dtype)
 
     def build():
@@ -233,12 +245,17 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
         + (WA * 8 if w.keep_rows is not None else 0)
     build_bytes = w.M * w.K * esz + kept_blocks * w.bw * esz + keep_in_b \
         + a_bits_b + colany_b + a_list_b + b_bits_b + bt_b
-    matmul_bytes = a_list_b + occ_b * w.bw * esz + colany_b + bt_b + w.M * w.N * 4
+    if path == mm.MMM_PATH_MATRIX:   # lists of A, occupied blocks of Y, the two small maps, C
+        matmul_bytes = a_list_b + occ_b * w.bw * esz + colany_b + bt_b + w.M * w.N * csz
+    else:                            # pair kernel: the non-zero elements of X, both bitmaps, occupied blocks of Y, C
+        matmul_bytes = nnz_a * esz + a_bits_b + bt_b + occ_b * w.bw * esz + w.M * w.N * csz
 
     # arithmetic peak the multiplication is priced against: fp32 inputs run on fp32 units (vector FMA and the fp32
     # matrix instruction share one peak); 16-bit inputs on the matrix path run on the 16-bit matrix instructions
     mfma16 = w.dtype != synth.DT_F32 and path == mm.MMM_PATH_MATRIX
     arith_peak, arith_name = (BF16_MFMA_PEAK_TFLOPS, "mfma") if mfma16 else (FP32_VECTOR_PEAK_TFLOPS, "alu")
+    if w.dtype == synth.DT_F64:
+        arith_peak = FP64_VECTOR_PEAK_TFLOPS
 
     def floors(nbytes, flops, t_ms):
         """Roofline of one kernel: the floor is the larger of the time its algorithmic bytes need at the HBM peak
@@ -271,7 +288,7 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
 
     row = {
         "workload": w.name, "M": w.M, "K": w.K, "N": w.N, "block_width": w.bw,
-        "dtype": {synth.DT_F32: "f32", synth.DT_BF16: "bf16", synth.DT_F16: "f16"}[w.dtype],
+        "dtype": {synth.DT_F32: "f32", synth.DT_BF16: "bf16", synth.DT_F16: "f16", synth.DT_F64: "f64"}[w.dtype],
         "nnz_a": nnz_a, "occupied_blocks_b": occ_b, "useful_macs": useful_macs,
         "a_density": nnz_a / (w.M * w.K), "b_block_density": occ_b / (w.K * NB),
         "path": "matrix" if path == mm.MMM_PATH_MATRIX else "pairs",
@@ -301,11 +318,12 @@ def measure(w, steps, warmup, args, dense=True, trials=True):
         def widen(t):     # device operand -> float32 values
             if w.dtype == synth.DT_BF16:
                 return (t.to(torch.int32) << 16).view(torch.float32)
-            return t.view(torch.float16).float() if w.dtype == synth.DT_F16 else t
+            return t.view(torch.float16).float() if w.dtype == synth.DT_F16 else t     # f32 and f64 as they are
 
         torch.cuda.synchronize()
-        A = torch.where(unpack(eng.a_bits(), w.K), widen(X), torch.zeros((), device="cuda"))
-        B = torch.where(unpack(eng.b_bits(), NB).repeat_interleave(w.bw, dim=1), widen(Y), torch.zeros((), device="cuda"))
+        zero = torch.zeros((), device="cuda", dtype=torch.float64 if w.dtype == synth.DT_F64 else torch.float32)
+        A = torch.where(unpack(eng.a_bits(), w.K), widen(X), zero)
+        B = torch.where(unpack(eng.b_bits(), NB).repeat_interleave(w.bw, dim=1), widen(Y), zero)
         if w.dtype == synth.DT_BF16:
             A, B = A.bfloat16(), B.bfloat16()
         elif w.dtype == synth.DT_F16:
@@ -396,7 +414,8 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default=None,
-                    help="one workload only: cfg1 | cfg2 | cfg3:<0..4>[:<0..4>] | cfg4 | cfg5 | colsparse | colsparse_bf16 "
+                    help="one workload only: cfg1 | cfg2 | cfg3:<0..4>[:<0..4>] | cfg4 | cfg5 | colsparse | colsparse_bf16 | "
+                         "cfg2_f64 | cfg3_f64:<0..4> "
                          "(default: the cfg3 sweep, then cfg2, cfg4 and cfg5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")

@@ -20,8 +20,8 @@
  *     compare them with what mmm_matmul is given.
  *   - Row-major; leading dimensions (ldx, ldy, ldc) are in elements and must be
  *     >= the row length; ldx and ldy must be below 2^22 (MMM_ERR_SHAPE
- *     otherwise, from mmm_build_maps and from mmm_matmul alike).  C is always
- *     float.
+ *     otherwise, from mmm_build_maps and from mmm_matmul alike).  C is float
+ *     (double for MMM_F64 inputs), passed as void*.
  *   - Bitmaps: LSB-first little-endian 64-bit words, row-major, every row padded
  *     to whole words, pad bits zero: bit (c mod 64) of word (c div 64) of row r
  *     describes column c of row r.  (The paper prints patterns first-vector-
@@ -62,8 +62,12 @@ typedef enum {
 
 /* Element type of X and Y.  BF16 is the upper half of an IEEE float, F16 the IEEE
  * half format; both are widened to float exactly, products are accumulated in
- * float. */
-typedef enum { MMM_F32 = 0, MMM_BF16 = 1, MMM_F16 = 2 } mmm_dtype;
+ * float and C is float.  F64: X, Y and C are double, products are accumulated in
+ * double (the paper reports float and double runs, section 4).  Double inputs
+ * are multiplied by the MMM_PATH_PAIRS kernel only, and mmm_build_maps writes the
+ * bitmaps and derived maps for them but no blocked lists (mmm_maps_view_lists is
+ * then meaningless) and does not use the row-compacted mode. */
+typedef enum { MMM_F32 = 0, MMM_BF16 = 1, MMM_F16 = 2, MMM_F64 = 3 } mmm_dtype;
 
 /* Element predicate of M.  An element of A is non-zero iff the predicate holds,
  * the optional keep bit is set, and the value is not +-0.  (Zero test by value:
@@ -215,7 +219,7 @@ mmm_status mmm_maps_stats(const mmm_maps *maps, uint64_t *nnz_a, uint64_t *occup
  * are not those of the build), MMM_ERR_DEVICE. */
 mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt,
                       const void *X, int64_t ldx, const void *Y, int64_t ldy,
-                      float *C, int64_t ldc, int32_t accumulate, void *hip_stream);
+                      void *C, int64_t ldc, int32_t accumulate, void *hip_stream);
 
 /* Which kernel mmm_matmul uses.
  *   MMM_PATH_MATRIX: matrix instructions over the compacted k lists of each 16-column group; skips
@@ -258,7 +262,7 @@ mmm_status mmm_matmul_path(const mmm_maps *maps, int32_t *path);
 mmm_status mmm_matmul_fused(const mmm_maps *maps, mmm_dtype dt,
                             const void *X, int64_t ldx, const mmm_mask_a *ma,
                             const void *Y, int64_t ldy,
-                            float *C, int64_t ldc, int32_t accumulate, void *hip_stream);
+                            void *C, int64_t ldc, int32_t accumulate, void *hip_stream);
 
 /* The same multiplication for callers that cannot allocate and must not have
  * memory allocated on their behalf while they run: code under HIP graph capture,
@@ -280,7 +284,7 @@ mmm_status mmm_matmul_fused(const mmm_maps *maps, mmm_dtype dt,
 #define MMM_STATIC_SCRATCH_BYTES (16u << 20)
 mmm_status mmm_matmul_static_scratch(const mmm_maps *maps, mmm_dtype dt,
                                      const void *X, int64_t ldx, const void *Y, int64_t ldy,
-                                     float *C, int64_t ldc, int32_t accumulate, void *hip_stream);
+                                     void *C, int64_t ldc, int32_t accumulate, void *hip_stream);
 
 /* Process-wide tuning knobs (for benchmarking; the defaults choose by shape).
  *   "matmul_variant": -1 = automatic, else index of a compiled tile variant

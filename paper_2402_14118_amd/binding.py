@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(PKG, "libmmm_hip.so")
 
 MMM_OK = 0
 MMM_ERR_INVALID_ARG, MMM_ERR_SHAPE, MMM_ERR_DTYPE, MMM_ERR_WORKSPACE, MMM_ERR_MAPS_MISMATCH, MMM_ERR_DEVICE = range(1, 7)
-MMM_F32, MMM_BF16, MMM_F16 = 0, 1, 2
+MMM_F32, MMM_BF16, MMM_F16, MMM_F64 = 0, 1, 2, 3
 MMM_PRED_NONZERO, MMM_PRED_GT, MMM_PRED_ABS_GT = 0, 1, 2
 MMM_PATH_AUTO, MMM_PATH_MATRIX, MMM_PATH_PAIRS = -1, 0, 1
 

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmmm_hip.so")
-SOURCES = ["mmm_api.hip", "mmm_build.hip", "mmm_matmul.hip", "mmm_pairs.hip"]
+SOURCES = ["mmm_api.hip", "mmm_build.hip", "mmm_matmul.hip", "mmm_pairs.hip", "mmm_build64.hip"]
 HEADERS = [os.path.join(CSRC, "mmm_internal.h"), os.path.join(ROOT, "include", "mmm.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

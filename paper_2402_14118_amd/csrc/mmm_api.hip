@@ -82,8 +82,9 @@ Layout make_layout(int64_t M, int64_t K, int64_t N, int32_t bw)
     return l;
 }
 
-bool dtype_ok(int32_t dt) { return dt == MMM_F32 || dt == MMM_BF16 || dt == MMM_F16; }
-size_t elem_size(int32_t dt) { return dt == MMM_F32 ? 4 : 2; }
+bool dtype_ok(int32_t dt) { return dt == MMM_F32 || dt == MMM_BF16 || dt == MMM_F16 || dt == MMM_F64; }
+size_t elem_size(int32_t dt) { return dt == MMM_F64 ? 8 : dt == MMM_F32 ? 4 : 2; }
+size_t c_elem_size(int32_t dt) { return dt == MMM_F64 ? 8 : 4; }
 
 mmm_plan make_plan(const mmm_maps *m, int32_t dt)
 {
@@ -275,10 +276,12 @@ mmm_status mmm_build_maps(mmm_maps *maps, mmm_dtype dt, const void *X, int64_t l
     // Row-compacted mode: when keep_rows switches whole rows of B off, the live rows are numbered k' and the
     // matrix kernel walks k' (steps of 128 live rows instead of 128 rows of which few are live).  The lists of
     // A are then made over k', so they are only good for the numbering they were made for.
-    a.b_compact = Y != nullptr && mb->keep_rows != nullptr;
+    a.b_compact = Y != nullptr && mb->keep_rows != nullptr && dt != MMM_F64;
     const bool compact_after = Y != nullptr ? a.b_compact : maps->b_compact;
     a.a_compact = X != nullptr && compact_after;
-    if (hipError_t e = mmm_launch_build(maps, a, static_cast<hipStream_t>(hip_stream)); e != hipSuccess) {
+    if (hipError_t e = dt == MMM_F64 ? mmm_launch_build64(maps, a, static_cast<hipStream_t>(hip_stream))
+                                      : mmm_launch_build(maps, a, static_cast<hipStream_t>(hip_stream));
+        e != hipSuccess) {
         note_device_error("map builder launch", e);
         return MMM_ERR_DEVICE;
     }
@@ -383,7 +386,7 @@ mmm_status mmm_matmul_plan(const mmm_maps *maps, mmm_dtype dt, int32_t *variant,
 }   // extern "C"
 
 static mmm_status matmul_common(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const void *Y, int64_t ldy,
-                                float *C, int64_t ldc, int32_t accumulate, void *hip_stream, bool static_scratch)
+                                void *C, int64_t ldc, int32_t accumulate, void *hip_stream, bool static_scratch)
 {
     if (maps == nullptr || X == nullptr || Y == nullptr || C == nullptr) return MMM_ERR_INVALID_ARG;
     if (!dtype_ok(dt)) return MMM_ERR_DTYPE;
@@ -391,13 +394,14 @@ static mmm_status matmul_common(const mmm_maps *maps, mmm_dtype dt, const void *
     if (ldx > kMaxLd || ldy > kMaxLd) return MMM_ERR_SHAPE;   // tile-relative offsets are 32-bit
     const size_t esz = elem_size(dt);
     if (reinterpret_cast<uintptr_t>(X) % esz != 0 || reinterpret_cast<uintptr_t>(Y) % esz != 0 ||
-        reinterpret_cast<uintptr_t>(C) % sizeof(float) != 0)
+        reinterpret_cast<uintptr_t>(C) % c_elem_size(dt) != 0)
         return MMM_ERR_DTYPE;
+    if (dt == MMM_F64 && !mmm_pairs_supports(dt, ldy)) return MMM_ERR_SHAPE;   // double inputs have the pair kernel only
     if (!maps->a_built || !maps->b_built) return MMM_ERR_MAPS_MISMATCH;
     if (maps->a_dtype != dt || maps->b_dtype != dt) return MMM_ERR_MAPS_MISMATCH;
     // the values of A travel in the lists that were copied from X at build time: another X is another A
     if (maps->a_src != X || maps->a_src_ld != ldx) return MMM_ERR_MAPS_MISMATCH;
-    if (choose_path(maps) == MMM_PATH_PAIRS && mmm_pairs_supports(dt, ldy)) {   // no scratch at all on this path
+    if (dt == MMM_F64 || (choose_path(maps) == MMM_PATH_PAIRS && mmm_pairs_supports(dt, ldy))) {   // no scratch at all on this path
         if (hipError_t e = mmm_launch_pairs(maps, dt, X, ldx, Y, ldy, C, ldc, accumulate ? 1 : 0, false, 0, 0.f, nullptr,
                                             static_cast<hipStream_t>(hip_stream));
             e != hipSuccess) {
@@ -423,7 +427,7 @@ static mmm_status matmul_common(const mmm_maps *maps, mmm_dtype dt, const void *
         }
         partial_bytes = (size_t)MMM_STATIC_SCRATCH_BYTES;
     }
-    if (hipError_t e = mmm_launch_matmul(maps, p, dt, X, ldx, Y, ldy, C, ldc, accumulate ? 1 : 0, partials,
+    if (hipError_t e = mmm_launch_matmul(maps, p, dt, X, ldx, Y, ldy, static_cast<float *>(C), ldc, accumulate ? 1 : 0, partials,
                                          partial_bytes, static_cast<hipStream_t>(hip_stream));
         e != hipSuccess) {
         note_device_error("masked GEMM launch", e);
@@ -435,13 +439,13 @@ static mmm_status matmul_common(const mmm_maps *maps, mmm_dtype dt, const void *
 extern "C" {
 
 mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const void *Y, int64_t ldy,
-                      float *C, int64_t ldc, int32_t accumulate, void *hip_stream)
+                      void *C, int64_t ldc, int32_t accumulate, void *hip_stream)
 {
     return matmul_common(maps, dt, X, ldx, Y, ldy, C, ldc, accumulate, hip_stream, false);
 }
 
 mmm_status mmm_matmul_fused(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const mmm_mask_a *ma,
-                            const void *Y, int64_t ldy, float *C, int64_t ldc, int32_t accumulate, void *hip_stream)
+                            const void *Y, int64_t ldy, void *C, int64_t ldc, int32_t accumulate, void *hip_stream)
 {
     if (maps == nullptr || X == nullptr || Y == nullptr || C == nullptr || ma == nullptr) return MMM_ERR_INVALID_ARG;
     if (ma->pred < MMM_PRED_NONZERO || ma->pred > MMM_PRED_ABS_GT) return MMM_ERR_INVALID_ARG;
@@ -451,7 +455,7 @@ mmm_status mmm_matmul_fused(const mmm_maps *maps, mmm_dtype dt, const void *X, i
     if (ldx > kMaxLd || ldy > kMaxLd) return MMM_ERR_SHAPE;
     const size_t esz = elem_size(dt);
     if (reinterpret_cast<uintptr_t>(X) % esz != 0 || reinterpret_cast<uintptr_t>(Y) % esz != 0 ||
-        reinterpret_cast<uintptr_t>(C) % sizeof(float) != 0)
+        reinterpret_cast<uintptr_t>(C) % c_elem_size(dt) != 0)
         return MMM_ERR_DTYPE;
     if (!mmm_pairs_supports(dt, ldy)) return MMM_ERR_SHAPE;
     if (!maps->b_built || maps->b_dtype != dt) return MMM_ERR_MAPS_MISMATCH;
@@ -465,7 +469,7 @@ mmm_status mmm_matmul_fused(const mmm_maps *maps, mmm_dtype dt, const void *X, i
 }
 
 mmm_status mmm_matmul_static_scratch(const mmm_maps *maps, mmm_dtype dt, const void *X, int64_t ldx, const void *Y,
-                                     int64_t ldy, float *C, int64_t ldc, int32_t accumulate, void *hip_stream)
+                                     int64_t ldy, void *C, int64_t ldc, int32_t accumulate, void *hip_stream)
 {
     return matmul_common(maps, dt, X, ldx, Y, ldy, C, ldc, accumulate, hip_stream, true);
 }
@@ -491,7 +495,7 @@ mmm_status mmm_maps_set_path(mmm_maps *maps, int32_t path)
 mmm_status mmm_matmul_path(const mmm_maps *maps, int32_t *path)
 {
     if (maps == nullptr || path == nullptr) return MMM_ERR_INVALID_ARG;
-    *path = choose_path(maps);
+    *path = (maps->a_built && maps->a_dtype == MMM_F64) || (maps->b_built && maps->b_dtype == MMM_F64) ? MMM_PATH_PAIRS : choose_path(maps);
     return MMM_OK;
 }
 

@@ -103,6 +103,9 @@ struct mmm_variant_info {
 };
 
 hipError_t mmm_launch_build(const mmm_maps *m, const mmm_build_args &a, hipStream_t s);
+// double-precision inputs: bitmaps, column-any words and the transposed map only (no lists)
+hipError_t mmm_launch_build64(const mmm_maps *m, const mmm_build_args &a, hipStream_t s);
+uint64_t mmm_threshold_key64(int32_t pred, float threshold);
 hipError_t mmm_launch_stats(const mmm_maps *m, hipStream_t s);
 int32_t mmm_variant_count();
 const mmm_variant_info &mmm_variant(int32_t i);
@@ -113,7 +116,7 @@ hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &p, int32_t dtype
 // The multiplication over exactly the surviving products, on the vector ALUs.  fused: evaluate M
 // (pred, threshold, keep_a) on X inside the kernel; otherwise a_bits of the maps are used.
 hipError_t mmm_launch_pairs(const mmm_maps *m, int32_t dtype, const void *X, int64_t ldx, const void *Y, int64_t ldy,
-                            float *C, int64_t ldc, int32_t accumulate, bool fused, int32_t pred, float threshold,
+                            void *C, int64_t ldc, int32_t accumulate, bool fused, int32_t pred, float threshold,
                             const uint64_t *keep_a, hipStream_t s);
 // whether that kernel can address a Y of this leading dimension (it forms 32-bit offsets inside 4096 rows)
 bool mmm_pairs_supports(int32_t dtype, int64_t ldy);

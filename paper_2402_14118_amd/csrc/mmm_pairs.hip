@@ -42,13 +42,13 @@ struct PairsParams {
     int64_t ldx;
     const void *Y;
     int64_t ldy;
-    float *C;
+    void *C;                  // float, or double for double inputs
     int64_t ldc;
     const uint64_t *a_bits;   // M x WA words (not FUSED)
     const uint64_t *keep_a;   // FUSED: optional keep bitmap of M, M x WA words
     const uint64_t *bt_bits;  // NB x WA words
     int64_t M, K, N, NB, WA;
-    uint32_t thr_bits;        // FUSED: threshold key of the predicate
+    uint64_t thr_bits;        // FUSED: threshold key of the predicate
     int32_t pred;
     int32_t accumulate;
 };
@@ -64,16 +64,44 @@ __device__ __forceinline__ uint32_t pairs_order_key(uint32_t u)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// The element predicate of M on the float bit pattern, non-zero test included (same decisions as
-// the map builder: integer compares, NaN fails > and |.| >, denormals are non-zero).
-__device__ __forceinline__ bool pairs_keep(int32_t pred, uint32_t u, uint32_t thr)
+__device__ __forceinline__ uint64_t pairs_order_key64(uint64_t u)
 {
-    const uint32_t a = u & 0x7fffffffu;
-    if (pred == MMM_PRED_NONZERO) return a != 0;
-    const bool ok = a != 0 && a <= 0x7f800000u;
-    if (pred == MMM_PRED_GT) return ok && pairs_order_key(u) > thr;
-    return ok && a > thr;
+    if ((u & 0x7fffffffffffffffull) == 0) u = 0;
+    return (u & 0x8000000000000000ull) ? ~u : (u | 0x8000000000000000ull);
 }
+
+// Per element type: the type products are accumulated in (float; double for double inputs), the exact
+// widening of an element to it, and the element predicate of M on the bit pattern, non-zero test
+// included (same decisions as the map builder: integer compares, NaN fails > and |.| >, denormals
+// are non-zero).  thr: the threshold key the host prepares (32-bit key in the low half for the float types).
+template <typename T> struct Elem {
+    typedef float acc;
+    static __device__ __forceinline__ acc value(T v) { return __uint_as_float(bits_of<T>(v)); }
+    static __device__ __forceinline__ bool keep(int32_t pred, T v, uint64_t thr64)
+    {
+        const uint32_t u = bits_of<T>(v), thr = (uint32_t)thr64;
+        const uint32_t a = u & 0x7fffffffu;
+        if (pred == MMM_PRED_NONZERO) return a != 0;
+        const bool ok = a != 0 && a <= 0x7f800000u;
+        if (pred == MMM_PRED_GT) return ok && pairs_order_key(u) > thr;
+        return ok && a > thr;
+    }
+    static __device__ __forceinline__ T zero() { return T(0); }
+};
+template <> struct Elem<double> {
+    typedef double acc;
+    static __device__ __forceinline__ acc value(double v) { return v; }
+    static __device__ __forceinline__ bool keep(int32_t pred, double v, uint64_t thr)
+    {
+        const uint64_t u = (uint64_t)__double_as_longlong(v);
+        const uint64_t a = u & 0x7fffffffffffffffull;
+        if (pred == MMM_PRED_NONZERO) return a != 0;
+        const bool ok = a != 0 && a <= 0x7ff0000000000000ull;
+        if (pred == MMM_PRED_GT) return ok && pairs_order_key64(u) > thr;
+        return ok && a > thr;
+    }
+    static __device__ __forceinline__ double zero() { return 0.0; }
+};
 
 __device__ __forceinline__ uint32_t pairs_xcd_id(uint32_t b, uint32_t n)
 {
@@ -93,11 +121,12 @@ __global__ __launch_bounds__(CW *KS * 64) void mmm_pairs_kernel(const PairsParam
     constexpr int CAP = LIST_SLOTS / G;        // entries per list and pass
     constexpr int WPL = WAVE_WORDS / BW;       // words per lane and range
     constexpr uint32_t ESZ = (uint32_t)sizeof(T);
+    typedef typename Elem<T>::acc acc_t;
     static_assert(CAP % U == 0, "a batch never leaves its list");
 
     __shared__ uint64_t aw[FUSED ? SUPER_WORDS : 1];   // FUSED: bitmap words of the row
     __shared__ __align__(16) uint16_t lists[NW][LIST_SLOTS];
-    __shared__ float red[KS > 1 ? (KS - 1) * CW * 64 : 1];
+    __shared__ acc_t red[KS > 1 ? (KS - 1) * CW * 64 : 1];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -123,7 +152,7 @@ __global__ __launch_bounds__(CW *KS * 64) void mmm_pairs_kernel(const PairsParam
     const char *Ycol = static_cast<const char *>(p.Y) + min(col0, p.N - 1) * ESZ;
     const uint32_t lane_off = blk_ok ? (uint32_t)lane * ESZ : 0u;
     uint16_t *lst = &lists[wave][g * CAP];
-    float acc = 0.f;
+    acc_t acc = 0;
 
     for (int64_t sw0 = 0; sw0 < p.WA; sw0 += SUPER_WORDS) {   // one trip unless FUSED and K > 65536
         const int sw = (int)min((int64_t)SUPER_WORDS, p.WA - sw0);
@@ -131,19 +160,19 @@ __global__ __launch_bounds__(CW *KS * 64) void mmm_pairs_kernel(const PairsParam
             __syncthreads();   // the words of the previous trip are no longer needed
             constexpr int PU = 8;   // words per trip: their loads are in flight together
             for (int w = wave; w < sw; w += PU * NW) {
-                uint32_t u[PU];
+                T u[PU];
                 uint64_t kp[PU];
 #pragma unroll
                 for (int q = 0; q < PU; ++q) {
                     const int64_t k = (sw0 + w + q * NW) * 64 + lane;
-                    u[q] = 0;
-                    if (w + q * NW < sw && k < p.K) u[q] = bits_of<T>(Xrow[k]);
+                    u[q] = Elem<T>::zero();
+                    if (w + q * NW < sw && k < p.K) u[q] = Xrow[k];
                     kp[q] = ~0ull;
                     if (p.keep_a != nullptr && w + q * NW < sw) kp[q] = p.keep_a[i * p.WA + sw0 + w + q * NW];
                 }
 #pragma unroll
                 for (int q = 0; q < PU; ++q) {
-                    const uint64_t m = __ballot(pairs_keep(p.pred, u[q], p.thr_bits)) & kp[q];   // lanes past K hold +0: never kept
+                    const uint64_t m = __ballot(Elem<T>::keep(p.pred, u[q], p.thr_bits)) & kp[q];   // lanes past K hold +0: never kept
                     if (lane == 0 && w + q * NW < sw) aw[w + q * NW] = m;
                 }
             }
@@ -222,33 +251,33 @@ __global__ __launch_bounds__(CW *KS * 64) void mmm_pairs_kernel(const PairsParam
                 for (; t + U <= rmin; t += U) {
                     const uint4 e4 = *reinterpret_cast<const uint4 *>(lst + t);
                     const uint32_t e[4] = {e4.x, e4.y, e4.z, e4.w};
-                    float a[U], b[U];
+                    acc_t a[U], b[U];
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         const uint32_t kb = (u & 1) ? (e[u >> 1] >> 16) : (e[u >> 1] & 0xffffu);   // k * ESZ
-                        a[u] = __uint_as_float(bits_of<T>(*reinterpret_cast<const T *>(Xr + kb)));
-                        b[u] = __uint_as_float(bits_of<T>(*reinterpret_cast<const T *>(Yr + (__umul24(kb, ldy) + lane_off))));
+                        a[u] = Elem<T>::value(*reinterpret_cast<const T *>(Xr + kb));
+                        b[u] = Elem<T>::value(*reinterpret_cast<const T *>(Yr + (__umul24(kb, ldy) + lane_off)));
                     }
 #pragma unroll
-                    for (int u = 0; u < U; ++u) acc = fmaf(a[u], b[u], acc);
+                    for (int u = 0; u < U; ++u) acc = __builtin_fma(a[u], b[u], acc);
                 }
                 // ragged ends: padded entries count for nothing, empty lists are switched off
                 for (; t < rend; t += U) {
-                    float a[U], b[U];
+                    acc_t a[U], b[U];
 #pragma unroll
-                    for (int u = 0; u < U; ++u) a[u] = b[u] = 0.f;
+                    for (int u = 0; u < U; ++u) a[u] = b[u] = 0;
                     if (alive) {
                         const uint4 e4 = *reinterpret_cast<const uint4 *>(lst + t);
                         const uint32_t e[4] = {e4.x, e4.y, e4.z, e4.w};
 #pragma unroll
                         for (int u = 0; u < U; ++u) {
                             const uint32_t kb = (u & 1) ? (e[u >> 1] >> 16) : (e[u >> 1] & 0xffffu);
-                            a[u] = __uint_as_float(bits_of<T>(*reinterpret_cast<const T *>(Xr + kb)));
-                            b[u] = __uint_as_float(bits_of<T>(*reinterpret_cast<const T *>(Yr + (__umul24(kb, ldy) + lane_off))));
+                            a[u] = Elem<T>::value(*reinterpret_cast<const T *>(Xr + kb));
+                            b[u] = Elem<T>::value(*reinterpret_cast<const T *>(Yr + (__umul24(kb, ldy) + lane_off)));
                         }
                     }
 #pragma unroll
-                    for (int u = 0; u < U; ++u) acc = fmaf(t + u < n_here ? a[u] : 0.f, b[u], acc);
+                    for (int u = 0; u < U; ++u) acc = __builtin_fma(t + u < n_here ? a[u] : acc_t(0), b[u], acc);
                 }
             }
         }
@@ -262,7 +291,7 @@ __global__ __launch_bounds__(CW *KS * 64) void mmm_pairs_kernel(const PairsParam
             for (int q = 1; q < KS; ++q) acc += red[((q - 1) * CW + cw) * 64 + lane];
     }
     if (ks == 0 && col < p.N) {
-        float *dst = p.C + i * p.ldc + col;
+        acc_t *dst = static_cast<acc_t *>(p.C) + i * p.ldc + col;
         *dst = p.accumulate ? *dst + acc : acc;
     }
 }
@@ -307,13 +336,13 @@ uint32_t pairs_threshold_key(int32_t pred, float threshold)
 
 bool mmm_pairs_supports(int32_t dtype, int64_t ldy)
 {
-    const int64_t esz = dtype == MMM_F32 ? 4 : 2;
+    const int64_t esz = dtype == MMM_F64 ? 8 : dtype == MMM_F32 ? 4 : 2;
     return ldy * esz * (MAX_WAVE_WORDS * 64) + 256 <= 0xffffffffLL;
 }
 
 // fused: evaluate M (pred, threshold, keep_a) on X in the kernel; otherwise take a_bits from the maps.
 hipError_t mmm_launch_pairs(const mmm_maps *m, int32_t dtype, const void *X, int64_t ldx, const void *Y, int64_t ldy,
-                            float *C, int64_t ldc, int32_t accumulate, bool fused, int32_t pred, float threshold,
+                            void *C, int64_t ldc, int32_t accumulate, bool fused, int32_t pred, float threshold,
                             const uint64_t *keep_a, hipStream_t s)
 {
     PairsParams p{};
@@ -332,7 +361,7 @@ hipError_t mmm_launch_pairs(const mmm_maps *m, int32_t dtype, const void *X, int
     p.NB = m->NB;
     p.WA = m->WA;
     p.pred = pred;
-    p.thr_bits = pairs_threshold_key(pred, threshold);
+    p.thr_bits = dtype == MMM_F64 ? mmm_threshold_key64(pred, threshold) : (uint64_t)pairs_threshold_key(pred, threshold);
     p.accumulate = accumulate;
     // Workgroups of 8 waves x 64 columns; when that gives the machine too little to do (few rows:
     // the decode shape), fewer columns per workgroup and K shared out over several waves.
@@ -345,10 +374,10 @@ hipError_t mmm_launch_pairs(const mmm_maps *m, int32_t dtype, const void *X, int
     if (wgs <= 0 || wgs > 0x7fffffffLL) return hipErrorInvalidValue;
     pairs_kernel_fn fn;
     if (fused)
-        fn = dtype == MMM_BF16 ? pick<uint16_t, true>(m->bw, shape) : dtype == MMM_F16 ? pick<_Float16, true>(m->bw, shape)
+        fn = dtype == MMM_F64 ? pick<double, true>(m->bw, shape) : dtype == MMM_BF16 ? pick<uint16_t, true>(m->bw, shape) : dtype == MMM_F16 ? pick<_Float16, true>(m->bw, shape)
                                                                                          : pick<float, true>(m->bw, shape);
     else
-        fn = dtype == MMM_BF16 ? pick<uint16_t, false>(m->bw, shape) : dtype == MMM_F16 ? pick<_Float16, false>(m->bw, shape)
+        fn = dtype == MMM_F64 ? pick<double, false>(m->bw, shape) : dtype == MMM_BF16 ? pick<uint16_t, false>(m->bw, shape) : dtype == MMM_F16 ? pick<_Float16, false>(m->bw, shape)
                                                                                           : pick<float, false>(m->bw, shape);
     (void)hipGetLastError();
     hipLaunchKernelGGL(fn, dim3((uint32_t)wgs), dim3((uint32_t)(sh.cw * sh.ks * 64)), 0, s, p);

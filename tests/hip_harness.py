@@ -8,8 +8,11 @@ import paper_2402_14118_amd as mm
 
 # fp32 inputs: the stated bound.  bf16 inputs: the stated bound.  IEEE half inputs: no bound is stated; the product of
 # two halves is exact in float and the sums are float sums, so the fp32 bound applies unchanged.
-TOL_REL = {synth.DT_F32: 1e-5, synth.DT_BF16: 1e-2, synth.DT_F16: 1e-5}
-TOL_ABS = 1e-6
+# Double inputs: none is stated either; products are accumulated by double FMAs over at most a few thousand terms
+# (error below terms * 2^-53 * |A||B|, i.e. 1e-12 leaves two decimal digits of room), and the absolute slack scales
+# with the precision.
+TOL_REL = {synth.DT_F32: 1e-5, synth.DT_BF16: 1e-2, synth.DT_F16: 1e-5, synth.DT_F64: 1e-12}
+TOL_ABS = {synth.DT_F32: 1e-6, synth.DT_BF16: 1e-6, synth.DT_F16: 1e-6, synth.DT_F64: 1e-15}
 
 
 def _dev(a, ld=None):
@@ -31,7 +34,10 @@ class HipRun:
 
     def __init__(self, w, ldx=None, ldy=None, ldc=None):
         self.w = w
-        if w.dtype != synth.DT_F32:
+        if w.dtype == synth.DT_F64:
+            self.X = _dev(np.asarray(w.X, dtype=np.float64), ldx)
+            self.Y = _dev(np.asarray(w.Y, dtype=np.float64), ldy)
+        elif w.dtype != synth.DT_F32:
             self.X = _dev(w.X_bits.view(np.int16), ldx)
             self.Y = _dev(w.Y_bits.view(np.int16), ldy)
         else:
@@ -41,7 +47,8 @@ class HipRun:
         self.keep_rows = _bits_dev(w.keep_rows)
         self.keep_blocks = _bits_dev(w.keep_blocks)
         ldc = ldc or w.N
-        self.Cbuf = torch.full((w.M, ldc), float("nan"), dtype=torch.float32, device="cuda")
+        self.Cbuf = torch.full((w.M, ldc), float("nan"), device="cuda",
+                               dtype=torch.float64 if w.dtype == synth.DT_F64 else torch.float32)
         self.C = self.Cbuf[:, : w.N]
         self.eng = mm.MaskedMatmul(w.M, w.K, w.N, w.bw, w.dtype)
 
@@ -77,7 +84,7 @@ class HipRun:
 
 def assert_close(C, C_ref, mag, dtype, what=""):
     err = np.abs(C.astype(np.float64) - C_ref.astype(np.float64))
-    bound = TOL_REL[dtype] * mag + TOL_ABS
+    bound = TOL_REL[dtype] * mag + TOL_ABS[dtype]
     bad = err > bound
     if bad.any():
         i = np.unravel_index(np.argmax(err - bound), err.shape)

@@ -79,7 +79,7 @@ def test_init_and_call_validation_without_device():
         assert L.mmm_maps_stats(maps, None, None, None, None) == B.MMM_ERR_MAPS_MISMATCH
         assert L.mmm_matmul(maps, 0, None, 128, Y, 64, C, 64, 0, None) == B.MMM_ERR_INVALID_ARG
         assert L.mmm_matmul(maps, 0, X, 128, Y, 64, C, 63, 0, None) == B.MMM_ERR_SHAPE
-        assert L.mmm_matmul(maps, 3, X, 128, Y, 64, C, 64, 0, None) == B.MMM_ERR_DTYPE
+        assert L.mmm_matmul(maps, 4, X, 128, Y, 64, C, 64, 0, None) == B.MMM_ERR_DTYPE      # 3 is MMM_F64
         assert L.mmm_matmul(None, 0, X, 128, Y, 64, C, 64, 0, None) == B.MMM_ERR_INVALID_ARG
         a, aw, b, bw = mm.mmm_maps_view(maps)
         assert a == fake and aw == 2 and bw == 1 and b > a

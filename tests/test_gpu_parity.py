@@ -79,7 +79,7 @@ def check_compacted(run, ab, bb, w, what):
     oracle's bitmaps and the keep_rows input."""
     comp = run.eng.compacted()
     live = live_rows(w)
-    if live is None:
+    if live is None or w.dtype == synth.DT_F64:     # double inputs do not use the mode
         assert comp is None, what
         return
     assert comp is not None, what
@@ -112,7 +112,7 @@ def check_workload(w, what, exact=False, **ld):
     np.testing.assert_array_equal(colany, exp_colany, err_msg=f"{what}: a_colany")
     np.testing.assert_array_equal(bt, exp_bt, err_msg=f"{what}: bt_bits")
     check_compacted(run, ab, bb, w, what)
-    if w.M * w.K <= 1 << 22:
+    if w.M * w.K <= 1 << 22 and w.dtype != synth.DT_F64:     # double inputs have no blocked lists
         check_lists(run, ab, w, what)
     assert run.eng.stats() == oracle.counts(ab, bb, w.M, w.K, w.N, w.bw), what
     if exact:
@@ -397,7 +397,7 @@ def test_automatic_path():
     assert run.eng.path() == mm.MMM_PATH_MATRIX       # a tile variant was asked for
     run.eng.set_plan()
     for p_a, p_b, want in [(0.02, 0.3, mm.MMM_PATH_PAIRS), (0.02, 0.02, mm.MMM_PATH_MATRIX), (0.2, 0.3, mm.MMM_PATH_MATRIX)]:
-        w = synth.random_masked(200, 600, 128, 16, p_a, p_b, 2, dist="smallint")
+        w = synth.random_masked(1024, 600, 2048, 16, p_a, p_b, 2, dist="smallint")
         run = HipRun(w)
         run.build()
         assert run.eng.path() == mm.MMM_PATH_MATRIX   # nothing counted yet
@@ -411,6 +411,13 @@ def test_automatic_path():
         run.eng.set_path(mm.MMM_PATH_MATRIX)
         assert run.eng.path() == mm.MMM_PATH_MATRIX
         run.eng.set_path()
+    # a small problem with short lists: latency-bound, the pair kernel (once the densities are known)
+    w = synth.random_masked(200, 600, 128, 16, 0.2, 0.3, 3, dist="smallint")
+    run = HipRun(w)
+    run.build()
+    assert run.eng.path() == mm.MMM_PATH_MATRIX
+    run.eng.stats()
+    assert run.eng.path() == mm.MMM_PATH_PAIRS
 
 
 FUSED_CASES = [(synth.PRED_NONZERO, 0.0, True), (synth.PRED_GT, 0.0, False), (synth.PRED_GT, -0.5, True),
@@ -461,6 +468,55 @@ def test_fused_exact_and_argument_checks():
     with pytest.raises(mm.MmmError) as e:
         run.eng.matmul_fused(run.X, run.Y, run.C, 3, 0.0, None)
     assert e.value.status == mm.binding.MMM_ERR_INVALID_ARG
+
+
+# ---- double-precision inputs (pair kernel only) -----------------------------------------------
+@pytest.mark.parametrize("M,K,N,bw", SHAPES)
+def test_f64_small_shapes(M, K, N, bw):
+    w = synth.random_masked(M, K, N, bw, 0.3, 0.4, 700 + M + K, dist="smallint", p_rows=0.8, dtype=synth.DT_F64)
+    run, _ = check_workload(w, f"f64 int {M}x{K}x{N} bw{bw}", exact=True)
+    assert run.eng.path() == mm.MMM_PATH_PAIRS and run.C.dtype == torch.float64
+    w = synth.random_masked(M, K, N, bw, 0.25, 0.3, 800 + N, dist="normal", dtype=synth.DT_F64)
+    check_workload(w, f"f64 {M}x{K}x{N} bw{bw}", ldx=K + 3, ldy=N + 5, ldc=N + 1)
+
+
+@pytest.mark.parametrize("bw,p_a,p_b,M,N", [(16, 0.9, 0.95, 5, 96), (8, 0.15, 0.5, 300, 2048), (32, 0.5, 0.1, 40, 160)])
+def test_f64_long_k(bw, p_a, p_b, M, N):
+    w = synth.random_masked(M, 9000, N, bw, p_a, p_b, 5250 + bw, dist="normal", dtype=synth.DT_F64)
+    check_workload(w, f"f64 long K bw {bw}")
+
+
+def test_f64_predicates_special_values_and_fused():
+    """Values float cannot hold: double denormals are non-zero, 1e300 passes the predicates; junk at masked positions;
+    the fused entry evaluates the same predicates on doubles."""
+    M, K, N, bw = 37, 700, 208, 16
+    for pred, thr, with_keep in FUSED_CASES:
+        w = synth.random_masked(M, K, N, bw, 0.4, 0.4, 4141, dist="normal", dtype=synth.DT_F64)
+        w.X[0, :8] = [0.0, -0.0, 1e-310, -1e-320, 4.9e-324, -2.0, 0.5, 1e300]
+        w.X[1, 5] = np.nan if pred != synth.PRED_NONZERO else 1.0
+        w.Y[3, 16:32] = 0.0
+        w.Y[3, 20] = 4.9e-324                    # a denormal occupies its block
+        w.pred, w.threshold = pred, thr
+        if not with_keep:
+            w.keep_a = None
+        ab, bb, C_ref, mag = oracle.run_workload(w)
+        keepb = np.repeat(synth.unpack_bits(w.keep_blocks, N // bw), bw, axis=1)
+        w.Y = np.where(keepb, w.Y, np.inf)       # switched-off blocks may hold anything
+        run = HipRun(w)
+        a_hip, b_hip, C = run.run()
+        np.testing.assert_array_equal(a_hip, ab, err_msg=f"f64 pred {pred} thr {thr}")
+        np.testing.assert_array_equal(b_hip, bb)
+        assert_close(C, C_ref, mag, w.dtype, f"f64 pred {pred} thr {thr}")
+        run.Cbuf.fill_(float("nan"))
+        run.eng.matmul_fused(run.X, run.Y, run.C, pred, thr, run.keep_a)
+        torch.cuda.synchronize()
+        assert_close(run.C.cpu().numpy(), C_ref, mag, w.dtype, f"f64 fused pred {pred} thr {thr}")
+
+
+def test_f64_config2_shape_full():
+    """The 2048^3 configuration in double precision, element by element."""
+    w = synth.random_masked(2048, 2048, 2048, 16, 0.1, 0.1, 1002, "normal", 0.0, 1.0, name="cfg2_f64", dtype=synth.DT_F64)
+    check_workload(w, "config 2 shape, f64")
 
 
 def test_autotune_fixes_a_plan_and_keeps_the_result():
