@@ -74,6 +74,9 @@ __device__ __forceinline__ uint64_t pairs_order_key64(uint64_t u)
 // widening of an element to it, and the element predicate of M on the bit pattern, non-zero test
 // included (same decisions as the map builder: integer compares, NaN fails > and |.| >, denormals
 // are non-zero).  thr: the threshold key the host prepares (32-bit key in the low half for the float types).
+__device__ __forceinline__ float fma_acc(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double fma_acc(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
 template <typename T> struct Elem {
     typedef float acc;
     static __device__ __forceinline__ acc value(T v) { return __uint_as_float(bits_of<T>(v)); }
@@ -259,7 +262,7 @@ __global__ __launch_bounds__(CW *KS * 64) void mmm_pairs_kernel(const PairsParam
                         b[u] = Elem<T>::value(*reinterpret_cast<const T *>(Yr + (__umul24(kb, ldy) + lane_off)));
                     }
 #pragma unroll
-                    for (int u = 0; u < U; ++u) acc = __builtin_fma(a[u], b[u], acc);
+                    for (int u = 0; u < U; ++u) acc = fma_acc(a[u], b[u], acc);
                 }
                 // ragged ends: padded entries count for nothing, empty lists are switched off
                 for (; t < rend; t += U) {
@@ -277,7 +280,7 @@ __global__ __launch_bounds__(CW *KS * 64) void mmm_pairs_kernel(const PairsParam
                         }
                     }
 #pragma unroll
-                    for (int u = 0; u < U; ++u) acc = __builtin_fma(t + u < n_here ? a[u] : acc_t(0), b[u], acc);
+                    for (int u = 0; u < U; ++u) acc = fma_acc(t + u < n_here ? a[u] : acc_t(0), b[u], acc);
                 }
             }
         }
