@@ -158,6 +158,10 @@ def test_every_variant_and_split(variant, split):
     run, _ = check_workload(w, f"variant {variant} split {split}", exact=True)
     v, s, _ = run.eng.plan()
     assert v == variant and s == split
+    # the same with rows of B switched off: the kernel walks the live rows only and shares them out over the splits
+    for p_rows in (0.5, 0.02):
+        w = synth.random_masked(30 if short else 150, 1500, 400, 16, 0.3, 0.5, 78, dist="smallint", p_rows=p_rows)
+        check_workload(w, f"variant {variant} split {split} rows {p_rows}", exact=True)
 
 
 @pytest.mark.parametrize("variant", range(mm.mmm_matmul_variant_count()))
@@ -587,13 +591,14 @@ def test_random_shapes_sweep():
         if variant >= 0 and mm.mmm_matmul_variant_name(variant).startswith("R2") and M > 32:
             variant = -1
         ld = dict(ldx=K + int(rng.integers(0, 9)), ldy=N + int(rng.integers(0, 9)), ldc=N + int(rng.integers(0, 9)))
+        p_rows = [None, None, 0.0, 0.1, 0.5, 1.0][int(rng.integers(0, 6))]     # whole rows of B switched off
         what = (f"sweep {it}: M={M} K={K} N={N} bw={bw} p_a={p_a} p_b={p_b} dtype={dtype} variant={variant} split={split} "
-                f"path={path} fused={fused} {ld}")
+                f"path={path} fused={fused} rows={p_rows} {ld}")
         print(what, flush=True)
         mm.mmm_set_option("matmul_variant", variant)
         mm.mmm_set_option("split_k", split)
         mm.mmm_set_option("matmul_path", path)
-        w = synth.random_masked(M, K, N, bw, p_a, p_b, 20000 + it, dist="smallint", dtype=dtype)
+        w = synth.random_masked(M, K, N, bw, p_a, p_b, 20000 + it, dist="smallint", dtype=dtype, p_rows=p_rows)
         ab, bb, C_ref, _ = oracle.run_workload(w)
         run = HipRun(w, **ld)
         a_hip, b_hip, C = run.run()
