@@ -457,6 +457,22 @@ def test_fused_mask_evaluation(pred, thr, with_keep, dtype):
     assert_close(run.C.cpu().numpy(), 2 * C_ref, 2 * mag, dtype, "fused accumulate")
 
 
+def test_row_stride_of_y_beyond_the_pair_kernels_reach():
+    """The pair kernel forms 32-bit offsets inside 4096 rows of Y; with a row stride of 2^18 floats and more the matrix
+    kernel multiplies whatever was asked for, and the fused entry (pair kernel only) refuses."""
+    w = synth.random_masked(40, 200, 64, 16, 0.3, 0.5, 88, dist="smallint")
+    _, _, C_ref, _ = oracle.run_workload(w)
+    run = HipRun(w, ldy=(1 << 18) + 8)
+    mm.mmm_set_option("matmul_path", mm.MMM_PATH_PAIRS)
+    run.build()
+    run.matmul()
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(run.C.cpu().numpy(), C_ref)
+    with pytest.raises(mm.MmmError) as e:
+        run.eng.matmul_fused(run.X, run.Y, run.C, w.pred, w.threshold, run.keep_a)
+    assert e.value.status == mm.binding.MMM_ERR_SHAPE
+
+
 def test_fused_exact_and_argument_checks():
     w = synth.random_masked(70, 700, 144, 8, 0.3, 0.4, 99, dist="smallint")
     _, _, C_ref, _ = oracle.run_workload(w)
