@@ -28,6 +28,8 @@
 // bitmaps, not the blocked lists of A.  With FUSED the mask M is evaluated right here (the
 // waves of a workgroup ballot the predicate over the row of X into LDS first), so no A-side map
 // pass is needed.
+#include <type_traits>
+
 #include "mmm_internal.h"
 
 namespace {
@@ -161,24 +163,34 @@ __global__ __launch_bounds__(CW *KS * 64) void mmm_pairs_kernel(const PairsParam
         const int sw = (int)min((int64_t)SUPER_WORDS, p.WA - sw0);
         if (FUSED) {
             __syncthreads();   // the words of the previous trip are no longer needed
+            // Every load below is unconditional (indices are clamped, results masked afterwards): a load
+            // inside a branch is waited for before the next one is issued.
             constexpr int PU = 8;   // words per trip: their loads are in flight together
-            for (int w = wave; w < sw; w += PU * NW) {
-                T u[PU];
-                uint64_t kp[PU];
+            auto ballots = [&](auto with_keep) __attribute__((always_inline)) {
+                for (int w = wave; w < sw; w += PU * NW) {
+                    T u[PU];
+                    uint64_t kp[PU];
 #pragma unroll
-                for (int q = 0; q < PU; ++q) {
-                    const int64_t k = (sw0 + w + q * NW) * 64 + lane;
-                    u[q] = Elem<T>::zero();
-                    if (w + q * NW < sw && k < p.K) u[q] = Xrow[k];
-                    kp[q] = ~0ull;
-                    if (p.keep_a != nullptr && w + q * NW < sw) kp[q] = p.keep_a[i * p.WA + sw0 + w + q * NW];
-                }
+                    for (int q = 0; q < PU; ++q) {
+                        const int wq = min(w + q * NW, sw - 1);
+                        const int64_t k = min((sw0 + wq) * 64 + lane, p.K - 1);
+                        u[q] = Xrow[k];
+                        kp[q] = ~0ull;
+                        if constexpr (decltype(with_keep)::value) kp[q] = p.keep_a[i * p.WA + sw0 + wq];
+                    }
 #pragma unroll
-                for (int q = 0; q < PU; ++q) {
-                    const uint64_t m = __ballot(Elem<T>::keep(p.pred, u[q], p.thr_bits)) & kp[q];   // lanes past K hold +0: never kept
-                    if (lane == 0 && w + q * NW < sw) aw[w + q * NW] = m;
+                    for (int q = 0; q < PU; ++q) {
+                        const int wq = w + q * NW;
+                        const bool inside = wq < sw && (sw0 + wq) * 64 + lane < p.K;   // lanes past K are never kept
+                        const uint64_t m = __ballot(inside && Elem<T>::keep(p.pred, u[q], p.thr_bits)) & kp[q];
+                        if (lane == 0 && wq < sw) aw[wq] = m;
+                    }
                 }
-            }
+            };
+            if (p.keep_a != nullptr)
+                ballots(std::true_type{});
+            else
+                ballots(std::false_type{});
             __syncthreads();
         }
         // this wave's ranges of the trip: ranges ks, ks + KS, ... of WAVE_WORDS words each
@@ -191,8 +203,9 @@ __global__ __launch_bounds__(CW *KS * 64) void mmm_pairs_kernel(const PairsParam
 #pragma unroll
             for (int j = 0; j < WPL; ++j) {
                 const int wi = rw0 + c + j * BW;
-                m[j] = 0;
-                if (wi < rw1 && blk_ok) m[j] = (FUSED ? aw[wi] : arow[sw0 + wi]) & btrow[sw0 + wi];
+                const int wic = min(wi, rw1 - 1);   // loaded unconditionally (a load inside a branch is waited for at once), masked below
+                const uint64_t wa = FUSED ? aw[wic] : arow[sw0 + wic], wb = btrow[sw0 + wic];
+                m[j] = wi < rw1 && blk_ok ? wa & wb : 0ull;
                 cnt += (uint32_t)__popcll(m[j]);
             }
             // ranks: exclusive prefix of the counts inside the lane group, and the group's total
