@@ -104,37 +104,47 @@ __device__ __forceinline__ void scan_a(const BuildParams &p, uint32_t b, int lan
     const T *X = static_cast<const T *>(p.X);
     const int64_t klim = MODE == A_LISTS ? (int64_t)*p.kinfo : p.K;   // number of (live) k
     if (MODE == A_LISTS && k_lo >= klim) return;                      // no live k left for this block (whole workgroup)
-    // keep words of the wave's 16 (row, half) pairs, one per lane 2j+h, requested together with X
+    // Every load below is unconditional: indices are clamped into the matrix and the results masked
+    // afterwards.  A load inside a branch is waited for before the next one is issued; written this way
+    // the wave's 16 row pieces and its keep words are all in flight together.
+    const bool has_keep = p.keep_a != nullptr;
+    // keep words of the wave's 16 (row, half) pairs, one per lane 2j+h (lanes 16.. repeat them; unused)
     uint64_t kw = ~0ull;
-    if (MODE != A_LISTS && p.keep_a != nullptr && lane < 2 * A_ROWS_PER_WAVE && rbase + (lane >> 1) < p.M &&
-        w_lo + (lane & 1) < p.WA)
-        kw = p.keep_a[(rbase + (lane >> 1)) * p.WA + w_lo + (lane & 1)];
-    int64_t korig[A_WORDS];   // A_LISTS: the original k of this lane's two columns
+    if (MODE != A_LISTS && has_keep) {   // wave-uniform
+        const int64_t kr = min(rbase + ((lane & 15) >> 1), p.M - 1), kwd = min(w_lo + (lane & 1), p.WA - 1);
+        kw = p.keep_a[kr * p.WA + kwd];
+    }
+    int64_t korig[A_WORDS];   // A_LISTS: the original k of this lane's two columns (-1: none)
 #pragma unroll
     for (int h = 0; h < A_WORDS; ++h) {
         const int64_t k = k_lo + 64 * h + lane;
-        korig[h] = k;
-        if (MODE == A_LISTS) korig[h] = k < klim ? (int64_t)p.kmap[k] : -1;
+        korig[h] = k < p.K ? k : -1;
+        if (MODE == A_LISTS) {
+            const uint32_t km = p.kmap[min(k, p.K - 1)];
+            korig[h] = k < klim ? (int64_t)km : -1;
+        }
     }
     uint32_t u[A_ROWS_PER_WAVE][A_WORDS];
+    uint32_t kbyte[A_ROWS_PER_WAVE][A_WORDS];   // A_LISTS with a keep bitmap: the byte that holds the element's keep bit
+#pragma unroll
+    for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
+#pragma unroll
+        for (int h = 0; h < A_WORDS; ++h) {
+            const int64_t rc = min(rbase + j, p.M - 1), kc = max(korig[h], (int64_t)0);
+            u[j][h] = f32_bits<T>(X[rc * p.ldx + kc]);
+            kbyte[j][h] = 0xffu;
+            if (MODE == A_LISTS && has_keep)   // wave-uniform
+                kbyte[j][h] = reinterpret_cast<const uint8_t *>(p.keep_a)[(rc * p.WA) * 8 + (kc >> 3)];
+        }
+    }
     uint32_t kbit[A_ROWS_PER_WAVE] = {};   // A_LISTS: keep bits of this lane's elements, bit h of entry j
 #pragma unroll
     for (int j = 0; j < A_ROWS_PER_WAVE; ++j) {
 #pragma unroll
         for (int h = 0; h < A_WORDS; ++h) {
-            const int64_t r = rbase + j, k = k_lo + 64 * h + lane;
-            u[j][h] = 0;
-            if (MODE == A_LISTS) {
-                if (r < p.M && korig[h] >= 0) {
-                    u[j][h] = f32_bits<T>(X[r * p.ldx + korig[h]]);
-                    uint32_t bit = 1;
-                    if (p.keep_a != nullptr)
-                        bit = (uint32_t)(reinterpret_cast<const uint8_t *>(p.keep_a)[(r * p.WA) * 8 + (korig[h] >> 3)] >> (korig[h] & 7)) & 1u;
-                    kbit[j] |= bit << h;
-                }
-            } else if (r < p.M && k < p.K) {
-                u[j][h] = f32_bits<T>(X[r * p.ldx + k]);
-            }
+            const bool inside = rbase + j < p.M && korig[h] >= 0;
+            if (!inside) u[j][h] = 0;   // +0: never kept
+            if (MODE == A_LISTS) kbit[j] |= (inside ? (kbyte[j][h] >> (korig[h] & 7)) & 1u : 0u) << h;
         }
     }
     uint64_t colany[A_WORDS] = {0, 0};
@@ -244,10 +254,13 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
     int64_t krow = -1;   // lane r: the row of Y behind the wave's row r (-1: none)
     {
         const int64_t kl = kbase + lane;
-        if (lane < B_ROWS_PER_WAVE) krow = COMPACT ? (kl < klive ? (int64_t)p.kmap[kl] : -1) : (kl < p.K ? kl : -1);
+        const int64_t kmapped = COMPACT ? (int64_t)p.kmap[min(kl, p.K - 1)] : kl;   // loaded unconditionally
+        if (lane < B_ROWS_PER_WAVE && kl < (COMPACT ? klive : p.K)) krow = kmapped;
         const bool mine = krow >= 0;
-        if (p.keep_rows != nullptr && mine) krw = p.keep_rows[krow >> 6];
-        if (p.keep_blocks != nullptr && mine) kbw = p.keep_blocks[krow * p.WB + w];
+        const int64_t kc = max(krow, (int64_t)0);   // unconditional loads at clamped rows, masked below
+        if (p.keep_rows != nullptr) krw = p.keep_rows[kc >> 6];        // wave-uniform branches
+        if (p.keep_blocks != nullptr) kbw = p.keep_blocks[kc * p.WB + w];
+        if (!mine) krw = kbw = ~0ull;
     }
     uint64_t kept[B_ROWS_PER_WAVE];
     int64_t korig[B_ROWS_PER_WAVE];
@@ -265,7 +278,7 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
                             (uint64_t)(uint32_t)__builtin_amdgcn_readlane((uint32_t)kbw, r);
         kept[r] = k >= 0 ? valid & kb & (0ull - ((kr >> (k & 63)) & 1ull)) : 0ull;
     }
-    constexpr int PER = BW <= 16 ? BW : 16;   // loads in flight per lane and row
+    constexpr int PER = BW <= 8 ? BW : 8;     // loads in flight per lane and row
 #pragma unroll
     for (int r = 0; r < B_ROWS_PER_WAVE; ++r) {
         const int64_t k = korig[r];
@@ -286,18 +299,23 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
                 if ((kept[r] >> lane) & 1ull) plist[mbcnt64(kept[r])] = (uint8_t)lane;
                 if (lane == 0) *res = 0;
                 const int slot = lane / BW;   // which of the load's blocks this lane reads
+                // Loads are unconditional, so that all of them are in flight together (a load inside a
+                // branch is waited for at once): slots past the end of the list read the first listed
+                // block again, which is a block that may be read, and are masked afterwards.
                 uint32_t u[ROUNDS];
                 int pos[ROUNDS];
+                T raw[ROUNDS];
 #pragma unroll
                 for (int t = 0; t < ROUNDS; ++t) {
                     const int j = t * BPL + slot;
-                    pos[t] = j < nkept ? (int)plist[j] : -1;
-                    u[t] = 0;
-                    if (pos[t] >= 0) {
-                        const T v = row[pos[t] * BW + lane % BW];
-                        u[t] = f32_bits<T>(v);
-                        if (COMPACT) crow[pos[t] * BW + lane % BW] = v;
-                    }
+                    const int pj = (int)plist[j < nkept ? j : 0];
+                    pos[t] = j < nkept ? pj : -1;
+                    raw[t] = row[pj * BW + lane % BW];
+                }
+#pragma unroll
+                for (int t = 0; t < ROUNDS; ++t) {
+                    u[t] = pos[t] >= 0 ? f32_bits<T>(raw[t]) : 0u;
+                    if (COMPACT && pos[t] >= 0) crow[pos[t] * BW + lane % BW] = raw[t];
                 }
 #pragma unroll
                 for (int t = 0; t < ROUNDS; ++t) {
@@ -311,16 +329,22 @@ __device__ __forceinline__ void scan_b(const BuildParams &p, uint32_t bb, int la
                 uint64_t mine = 0;
 #pragma unroll
                 for (int j0 = 0; j0 < BW; j0 += PER) {
+                    // unconditional loads (see above): lanes whose block is switched off read the first
+                    // switched-on block of the word instead, and are masked afterwards
                     uint32_t u[PER];
+                    T raw[PER];
+                    const int first_on = __builtin_ctzll(kept[r]) * BW + lane % BW;
 #pragma unroll
                     for (int j = 0; j < PER; ++j) {
                         const int blk = (j0 + j) * BPL + lane / BW;   // block (inside this word) of this lane's element
-                        u[j] = 0;
-                        if ((kept[r] >> blk) & 1ull) {
-                            const T v = row[(j0 + j) * 64 + lane];
-                            u[j] = f32_bits<T>(v);
-                            if (COMPACT) crow[(j0 + j) * 64 + lane] = v;
-                        }
+                        raw[j] = row[(kept[r] >> blk) & 1ull ? (j0 + j) * 64 + lane : first_on];
+                    }
+#pragma unroll
+                    for (int j = 0; j < PER; ++j) {
+                        const int blk = (j0 + j) * BPL + lane / BW;
+                        const bool on = (kept[r] >> blk) & 1ull;
+                        u[j] = on ? f32_bits<T>(raw[j]) : 0u;
+                        if (COMPACT && on) crow[(j0 + j) * 64 + lane] = raw[j];
                     }
 #pragma unroll
                     for (int j = 0; j < PER; ++j) {
