@@ -38,9 +38,11 @@ __global__ __launch_bounds__(256) void mmm_build64_a_kernel(const double *X, int
     uint64_t u[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
+        // loaded unconditionally at a clamped position and masked afterwards: a load inside a branch is
+        // waited for before the next one is issued
         const int64_t r = t * 32 + wave * 8 + j;
-        u[j] = 0;
-        if (r < M && k < K) u[j] = (uint64_t)__double_as_longlong(X[r * ldx + k]);
+        u[j] = (uint64_t)__double_as_longlong(X[min(r, M - 1) * ldx + min(k, K - 1)]);
+        if (r >= M || k >= K) u[j] = 0;
     }
     uint64_t colany = 0;
 #pragma unroll
@@ -78,13 +80,23 @@ __global__ __launch_bounds__(256) void mmm_build64_b_kernel(const double *Y, int
         const double *row = Y + k * ldy + w * 64 * BW;
         const uint64_t bwmask = BW == 32 ? 0xffffffffull : ((1ull << BW) - 1ull);
         uint64_t mine = 0;
+        // unconditional loads, eight in flight: lanes whose block is switched off read the first switched-on
+        // block of the word instead (a block that may be read) and are masked afterwards
+        const int first_on = __builtin_ctzll(kept) * BW + lane % BW;
 #pragma unroll
-        for (int j = 0; j < BW; ++j) {   // load j holds the blocks j * BPL .. j * BPL + BPL - 1 of the word
-            const int blk = j * BPL + lane / BW;
-            uint64_t u = 0;
-            if ((kept >> blk) & 1ull) u = (uint64_t)__double_as_longlong(row[j * 64 + lane]);
-            const uint64_t m = __ballot((u & 0x7fffffffffffffffull) != 0);
-            if (lane / BPL == j) mine = m;   // lane L collects the load that holds block L
+        for (int j0 = 0; j0 < BW; j0 += 8) {
+            uint64_t u[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {   // load j0 + j holds the blocks (j0 + j) * BPL .. of the word
+                const int blk = (j0 + j) * BPL + lane / BW;
+                u[j] = (uint64_t)__double_as_longlong(row[(kept >> blk) & 1ull ? (j0 + j) * 64 + lane : first_on]);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int blk = (j0 + j) * BPL + lane / BW;
+                const uint64_t m = __ballot(((kept >> blk) & 1ull) && (u[j] & 0x7fffffffffffffffull) != 0);
+                if (lane / BPL == j0 + j) mine = m;   // lane L collects the load that holds block L
+            }
         }
         word = __ballot(((mine >> ((lane % BPL) * BW)) & bwmask) != 0);
     }
