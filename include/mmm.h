@@ -235,7 +235,7 @@ mmm_status mmm_matmul(const mmm_maps *maps, mmm_dtype dt,
  * "matmul_variant" option).  Else, with p_A and p_B the densities of A's elements and B's
  * blocks counted by the most recent mmm_maps_stats call on the handle (kept as the estimate
  * across rebuilds): for matrices of at most 64 rows PAIRS unless p_A * p_B is known to exceed
- * 0.02; for larger ones PAIRS iff the densities are known and p_B * (1 - 24.5 * p_A) > 0.035
+ * 0.02; for larger ones PAIRS iff the densities are known and p_B * (1 - 24.5 * p_A) > 0.015
  * (A keeps fewer than 4 % of its elements and B is not nearly empty), or the problem is small
  * (fewer than 128 tiles of 64 x 128 in C) with at most 64 surviving k per element of C; else MATRIX.  The
  * thresholds are fitted to timings on an MI355X.  The paper leaves this

@@ -136,8 +136,8 @@ mmm_plan make_plan(const mmm_maps *m, int32_t dt)
 // proportion to the product of both densities but pays two gathers per product and a fixed cost
 // per row and 64 columns.  Fitted to measurements on an MI355X (4096^3, 2048 x 16384 x 4096 and
 // 32 ... 512 x 8192 x 4096, densities 0.02 ... 0.4):
-//     pairs  ~ 130 us + 24500 us * p_A * p_B      matrix ~ 95 us + 1000 us * p_B      (per 4096^3)
-// so for matrices of many rows the pair kernel is ahead iff p_B * (1 - 24.5 * p_A) > 0.035, which
+//     pairs  ~ 110 us + 24500 us * p_A * p_B      matrix ~ 95 us + 1000 us * p_B      (per 4096^3)
+// so for matrices of many rows the pair kernel is ahead iff p_B * (1 - 24.5 * p_A) > 0.015, which
 // needs p_A below 0.04; for matrices of at most 64 rows (one tile of the matrix kernel, mostly
 // empty, and a latency-bound launch) it is ahead up to p_A * p_B of about 0.02, and for small problems
 // (256^3) with short lists as well.  Densities are
@@ -157,7 +157,7 @@ int32_t choose_path(const mmm_maps *m)
     // latency, of which the pair kernel has less
     const int64_t tiles = ((m->M + 63) / 64) * ((m->N + 127) / 128);
     if (known && tiles < 128 && p_a * p_b * (double)m->K <= 64.0) return MMM_PATH_PAIRS;
-    return known && p_b * (1.0 - 24.5 * p_a) > 0.035 ? MMM_PATH_PAIRS : MMM_PATH_MATRIX;
+    return known && p_b * (1.0 - 24.5 * p_a) > 0.015 ? MMM_PATH_PAIRS : MMM_PATH_MATRIX;
 }
 
 }   // namespace
