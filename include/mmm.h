@@ -100,8 +100,11 @@ typedef struct {
 /* Host-side handle describing maps that live in caller-provided device memory. */
 typedef struct mmm_maps mmm_maps;
 
-/* Bytes of device workspace that maps for this shape need (maps, their derived
- * forms, and the partial-sum area of the split-K multiplication).
+/* Bytes of device workspace that maps for this shape need: the maps and their
+ * derived forms, the blocked lists of A at their worst-case size (16 bytes per
+ * element of X), room for the row-compacted copy of Y (4 bytes per element of
+ * Y, used only when keep_rows is given), and the partial-sum area of the split-K
+ * multiplication (at most 64 MiB).
  * Errors: MMM_ERR_SHAPE, MMM_ERR_INVALID_ARG (bytes NULL). */
 mmm_status mmm_maps_workspace_bytes(int64_t M, int64_t K, int64_t N, int32_t block_width, size_t *bytes);
 
