@@ -101,7 +101,7 @@ typedef struct {
 typedef struct mmm_maps mmm_maps;
 
 /* Bytes of device workspace that maps for this shape need: the maps and their
- * derived forms, the blocked lists of A at their worst-case size (16 bytes per
+ * derived forms, the blocked lists of A at their worst-case size (8 bytes per
  * element of X), room for the row-compacted copy of Y (4 bytes per element of
  * Y, used only when keep_rows is given), and the partial-sum area of the split-K
  * multiplication (at most 64 MiB).
