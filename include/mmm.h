@@ -178,6 +178,23 @@ mmm_status mmm_maps_view_compacted(const mmm_maps *maps, int32_t *on, const uint
                                    const uint32_t **kmap, const uint64_t **a_colany_c,
                                    const uint64_t **btc_bits);
 
+/* The per-tile active-k lists, for inspection.  The matrix kernel walks, for every row tile
+ * of 64 rows, every group of 16 columns and every step of 128 values of k (of k' in
+ * row-compacted mode), the ascending list of the k in that step for which the group's
+ * block(s) of B are occupied and some row of the tile has a non-zero element of A; it makes
+ * these lists itself, a window of steps at a time, from the transposed B map and the
+ * column-any words.  This call runs exactly that list construction (for the default tile
+ * shape) and writes the lists to `out` (device memory) instead of multiplying:
+ *     record (tile t, group G, step c) at byte ((t * groups + G) * steps + c) * 132, where
+ *     groups = 16 * ceil(N / 256), steps = ceil(K / 128):
+ *     uint32 count, then `count` bytes k - 128 c (ascending), then unspecified bytes.
+ *     Records of steps past the last live step (row-compacted mode) are not written.
+ * Call with out == NULL to learn the size in *bytes_needed.  Both sides must be built.
+ * Errors: MMM_ERR_INVALID_ARG, MMM_ERR_MAPS_MISMATCH, MMM_ERR_DTYPE (double inputs),
+ * MMM_ERR_WORKSPACE (out too small), MMM_ERR_DEVICE. */
+mmm_status mmm_debug_k_lists(const mmm_maps *maps, void *out, size_t out_bytes, size_t *bytes_needed,
+                             void *hip_stream);
+
 /* Device pointers to the blocked non-zero lists of A, for inspection.  A is cut
  * into *blocks_m x *blocks_k blocks of 64 rows x 128 columns (ragged at the far
  * edges); block (bm, bk) has index bm * *blocks_k + bk.

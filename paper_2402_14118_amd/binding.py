@@ -27,7 +27,7 @@ MMM_PATH_AUTO, MMM_PATH_MATRIX, MMM_PATH_PAIRS = -1, 0, 1
 
 EXPORTS = [
     "mmm_maps_workspace_bytes", "mmm_maps_init", "mmm_maps_release", "mmm_build_maps", "mmm_maps_view",
-    "mmm_maps_view_derived", "mmm_maps_view_compacted", "mmm_maps_view_lists", "mmm_maps_stats", "mmm_matmul", "mmm_matmul_static_scratch", "mmm_matmul_fused",
+    "mmm_maps_view_derived", "mmm_maps_view_compacted", "mmm_maps_view_lists", "mmm_debug_k_lists", "mmm_maps_stats", "mmm_matmul", "mmm_matmul_static_scratch", "mmm_matmul_fused",
     "mmm_maps_set_path", "mmm_matmul_path", "mmm_set_option", "mmm_matmul_variant_count",
     "mmm_matmul_variant_name", "mmm_matmul_plan", "mmm_maps_set_plan", "mmm_status_string", "mmm_last_device_error",
 ]
@@ -66,6 +66,7 @@ def _load() -> ctypes.CDLL:
     lib.mmm_maps_view.argtypes = [vp, c.POINTER(vp), c.POINTER(i64), c.POINTER(vp), c.POINTER(i64)]
     lib.mmm_maps_view_derived.argtypes = [vp, c.POINTER(vp), c.POINTER(vp), c.POINTER(i64)]
     lib.mmm_maps_view_compacted.argtypes = [vp, c.POINTER(i32), c.POINTER(vp), c.POINTER(vp), c.POINTER(vp), c.POINTER(vp)]
+    lib.mmm_debug_k_lists.argtypes = [vp, vp, c.c_size_t, c.POINTER(c.c_size_t), vp]
     lib.mmm_maps_view_lists.argtypes = [vp, c.POINTER(vp), c.POINTER(vp), c.POINTER(i64), c.POINTER(i64), c.POINTER(i64)]
     lib.mmm_maps_stats.argtypes = [vp, c.POINTER(c.c_uint64), c.POINTER(c.c_uint64), c.POINTER(c.c_uint64), vp]
     lib.mmm_matmul.argtypes = [vp, i32, vp, i64, vp, i64, vp, i64, i32, vp]
@@ -167,6 +168,13 @@ def mmm_maps_view_compacted(maps: int):
     _check(lib.mmm_maps_view_compacted(maps, ctypes.byref(on), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c_),
                                        ctypes.byref(d)), "mmm_maps_view_compacted")
     return bool(on.value), a.value, b.value, c_.value, d.value
+
+
+def mmm_debug_k_lists(maps: int, out=None, out_bytes: int = 0, stream=None) -> int:
+    """Writes the matrix kernel's k lists to `out` (device memory); returns the bytes needed (out=None: only that)."""
+    need = ctypes.c_size_t(0)
+    _check(lib.mmm_debug_k_lists(maps, _ptr(out), out_bytes, ctypes.byref(need), _stream(stream)), "mmm_debug_k_lists")
+    return need.value
 
 
 def mmm_maps_view_lists(maps: int):

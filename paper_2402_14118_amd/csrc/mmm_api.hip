@@ -337,6 +337,23 @@ mmm_status mmm_maps_view_compacted(const mmm_maps *maps, int32_t *on, const uint
     return MMM_OK;
 }
 
+mmm_status mmm_debug_k_lists(const mmm_maps *maps, void *out, size_t out_bytes, size_t *bytes_needed, void *hip_stream)
+{
+    if (maps == nullptr) return MMM_ERR_INVALID_ARG;
+    if (!maps->a_built || !maps->b_built) return MMM_ERR_MAPS_MISMATCH;
+    if (maps->a_dtype == MMM_F64) return MMM_ERR_DTYPE;   // double inputs have no matrix kernel
+    size_t need = 0;
+    const hipError_t e = mmm_launch_dump_lists(maps, static_cast<uint8_t *>(out), out_bytes, &need,
+                                               static_cast<hipStream_t>(hip_stream));
+    if (bytes_needed) *bytes_needed = need;
+    if (e == hipErrorInvalidValue) return out == nullptr && bytes_needed != nullptr ? MMM_OK : MMM_ERR_WORKSPACE;
+    if (e != hipSuccess) {
+        note_device_error("k list dump launch", e);
+        return MMM_ERR_DEVICE;
+    }
+    return MMM_OK;
+}
+
 mmm_status mmm_maps_view_lists(const mmm_maps *maps, const uint32_t **counts, const uint64_t **entries,
                                int64_t *blocks_m, int64_t *blocks_k, int64_t *capacity)
 {

@@ -120,5 +120,7 @@ hipError_t mmm_launch_pairs(const mmm_maps *m, int32_t dtype, const void *X, int
                             const uint64_t *keep_a, hipStream_t s);
 // whether that kernel can address a Y of this leading dimension (it forms 32-bit offsets inside 4096 rows)
 bool mmm_pairs_supports(int32_t dtype, int64_t ldy);
+// the k lists the matrix kernel's default tile shape walks, written out (need: bytes required)
+hipError_t mmm_launch_dump_lists(const mmm_maps *m, uint8_t *out, size_t out_bytes, size_t *need, hipStream_t s);
 // device address of the library's own scratch array on the current device (MMM_STATIC_SCRATCH_BYTES bytes)
 hipError_t mmm_static_scratch(float **ptr);

@@ -62,6 +62,7 @@ struct MatmulParams {
     const uint64_t *a_colany;
     const uint64_t *b_bits;
     const uint64_t *bt_bits;
+    uint8_t *dump;           // DUMP instantiation only: where the k lists are written out (see mmm_debug_k_lists)
     const uint32_t *kinfo;   // row-compacted mode: [0] = number of live k (the maps, lists and Y above are then over k'); else null
     int64_t M, K, N, NB, WA, WB, MT, KBA;
     int32_t bw;
@@ -127,7 +128,7 @@ constexpr int list_words(int nw) { return nw == 8 ? 16 : 32; }
 //
 // RT  16-row MFMA sub-tiles computed (4: all 64 rows of the block; 2: matrices of at most 32 rows)
 // GW  16-column groups per wave, NW waves per workgroup: TN = 16*GW*NW columns
-template <int RT, int GW, int NW, typename T, bool BW8>
+template <int RT, int GW, int NW, typename T, bool BW8, bool DUMP = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8 && GW == 1 ? 4 : 2))) void mmm_matmul_kernel(const MatmulParams p)
 {
     constexpr int NG = NW * GW;
@@ -481,6 +482,31 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW >= 8
         Ycur += ystride;
     };
 
+    if constexpr (DUMP) {
+        // Inspection only: write out the k lists exactly as build_lists makes them, window by window, and
+        // multiply nothing.  Record of (row tile, 16-column group, step): 4-byte count, then 128 list bytes.
+        for (int wb = chunk_begin; wb < chunk_end; wb += p.window_chunks) {
+            wbegin = wb;
+            wchunks = min(p.window_chunks, chunk_end - wb);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();   // the previous window's lists have been copied out
+            build_lists(wb, wchunks);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int g = 0; g < GW; ++g) {
+                const int64_t G = (int64_t)tile_n * NG + wave * GW + g;
+                for (int ci = 0; ci < wchunks; ++ci) {
+                    int start, n;
+                    step_range(ci, g, start, n);
+                    uint8_t *rec = p.dump + ((((int64_t)tile_m * p.tiles_n * NG + G) * p.chunks_total) + wb + ci) * 132;
+                    if (lane == 0) *reinterpret_cast<uint32_t *>(rec) = (uint32_t)n;
+                    for (int e = lane; e < n; e += 64) rec[4 + e] = lists[wave][g * REGION + start + e];
+                }
+            }
+        }
+        return;
+    }
     if (chunk_begin < chunk_end) {
         issue_entries(chunk_begin, E1);
         issue_entries(chunk_begin + 1, E2);
@@ -626,6 +652,38 @@ hipError_t mmm_static_scratch(float **ptr)
 
 int32_t mmm_variant_count() { return kVariants; }
 const mmm_variant_info &mmm_variant(int32_t i) { return g_variants[i].info; }
+
+// The k lists of the default tile shape (64 x 256, sixteen waves), written out for inspection.
+hipError_t mmm_launch_dump_lists(const mmm_maps *m, uint8_t *out, size_t out_bytes, size_t *need, hipStream_t s)
+{
+    constexpr int NG = 16;
+    MatmulParams p{};
+    p.a_colany = m->b_compact ? m->a_colany_c : m->a_colany;
+    p.bt_bits = m->b_compact ? m->btc_bits : m->bt_bits;
+    p.kinfo = m->b_compact ? m->kinfo : nullptr;
+    p.M = m->M;
+    p.K = m->K;
+    p.N = m->N;
+    p.NB = m->NB;
+    p.WA = m->WA;
+    p.WB = m->WB;
+    p.MT = m->MT;
+    p.KBA = m->KBA;
+    p.bw = m->bw;
+    p.tiles_m = (int32_t)((m->M + TM - 1) / TM);
+    p.tiles_n = (int32_t)((m->N + 16 * NG - 1) / (16 * NG));
+    p.split_k = 1;
+    p.chunks_total = (int32_t)((m->K + KC - 1) / KC);
+    p.chunks_per_split = p.chunks_total;
+    p.window_chunks = (int32_t)(list_words(NG) / WPC);
+    p.dump = out;
+    const size_t bytes = (size_t)p.tiles_m * (size_t)p.tiles_n * NG * (size_t)p.chunks_total * 132;
+    if (need) *need = bytes;
+    if (out == nullptr || out_bytes < bytes) return hipErrorInvalidValue;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL((mmm_matmul_kernel<4, 1, 16, float, false, true>), dim3((uint32_t)(p.tiles_m * p.tiles_n)), dim3(1024), 0, s, p);
+    return hipGetLastError();
+}
 
 hipError_t mmm_launch_matmul(const mmm_maps *m, const mmm_plan &pl, int32_t dtype, const void *X, int64_t ldx,
                              const void *Y, int64_t ldy, float *C, int64_t ldc, int32_t accumulate, float *partials,

@@ -139,6 +139,15 @@ class MaskedMatmul:
                 view(ca, ((self.M + 31) // 32) * wa * 8, torch.int64).view(-1, wa),
                 view(bt, (self.N // self.bw) * wa * 8, torch.int64).view(-1, wa))
 
+    def k_lists(self) -> torch.Tensor:
+        """The matrix kernel's per-tile active-k lists as uint8 [row tiles, column groups, steps, 132] (4-byte count,
+        then the list bytes); see mmm_debug_k_lists."""
+        need = B.mmm_debug_k_lists(self.maps)
+        out = torch.zeros(need, dtype=torch.uint8, device=self.device)
+        B.mmm_debug_k_lists(self.maps, out, need)
+        tm, groups, steps = (self.M + 63) // 64, 16 * ((self.N + 255) // 256), (self.K + 127) // 128
+        return out.view(tm, groups, steps, 132)
+
     def a_lists(self):
         """(counts int32 [blocks_m, blocks_k], entries int64 [blocks_m * blocks_k, capacity]) as views of the workspace."""
         c, e, bm, bk, cap = B.mmm_maps_view_lists(self.maps)

@@ -100,6 +100,43 @@ def check_compacted(run, ab, bb, w, what):
     np.testing.assert_array_equal(btc.view(np.uint64)[:, :have], exp_b[:, :have], err_msg=f"{what}: bt_bits over k'")
 
 
+def check_k_lists(run, ab, bb, w, what):
+    """The per-tile active-k lists the matrix kernel walks, as its own list construction writes them out: for every row
+    tile of 64, 16-column group and step of 128 the ascending k with (some non-zero of A in the tile's column k) and
+    (the group's block(s) of B occupied in row k) -- over the live rows k' when keep_rows is given.  Expected lists
+    come from the oracle's bitmaps alone."""
+    got = run.eng.k_lists().cpu().numpy()
+    NB, bw = w.N // w.bw, w.bw
+    a = synth.unpack_bits(ab, w.K)
+    b = synth.unpack_bits(bb, NB)
+    live = live_rows(w)
+    if live is not None:
+        a, b = a[:, live], b[live]
+    kk = a.shape[1]
+    tm, groups, steps = got.shape[:3]
+    assert tm == (w.M + 63) // 64 and groups == 16 * ((w.N + 255) // 256) and steps == (w.K + 127) // 128, what
+    pad = (-w.M) % 64
+    a64 = np.concatenate([a, np.zeros((pad, kk), bool)]) if pad else a
+    colany = a64.reshape(tm, 64, kk).any(axis=1)                      # [tile, k]
+    for G in range(groups):
+        if G * 16 >= w.N:
+            occ = np.zeros(kk, bool)
+        elif bw == 16:
+            occ = b[:, G]
+        elif bw == 32:
+            occ = b[:, G // 2]
+        else:
+            occ = b[:, 2 * G] | (b[:, 2 * G + 1] if 2 * G + 1 < NB else False)
+        for t in range(tm):
+            active = colany[t] & occ
+            for c in range((kk + 127) // 128):                        # steps past the last live one are not written
+                want = np.nonzero(active[128 * c: 128 * c + 128])[0]
+                rec = got[t, G, c]
+                n = int(rec[:4].view(np.uint32)[0])
+                assert n == len(want), f"{what}: k list of tile {t} group {G} step {c}: {n} entries, want {len(want)}"
+                np.testing.assert_array_equal(rec[4: 4 + n], want.astype(np.uint8), err_msg=f"{what}: k list ({t},{G},{c})")
+
+
 def check_workload(w, what, exact=False, **ld):
     print(f"case {what}: M={w.M} K={w.K} N={w.N} bw={w.bw} dtype={w.dtype}", flush=True)
     ab, bb, C_ref, mag = oracle.run_workload(w)
@@ -114,6 +151,8 @@ def check_workload(w, what, exact=False, **ld):
     check_compacted(run, ab, bb, w, what)
     if w.M * w.K <= 1 << 22 and w.dtype != synth.DT_F64:     # double inputs have no blocked lists
         check_lists(run, ab, w, what)
+        if w.M * w.K * (w.N // 16) <= 1 << 26:
+            check_k_lists(run, ab, bb, w, what)
     assert run.eng.stats() == oracle.counts(ab, bb, w.M, w.K, w.N, w.bw), what
     if exact:
         np.testing.assert_array_equal(C, C_ref, err_msg=what)
