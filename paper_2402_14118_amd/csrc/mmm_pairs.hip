@@ -321,10 +321,11 @@ template <typename T, int BW, bool FUSED> pairs_kernel_fn pick_shape(int shape)
     switch (shape) {
     case 1: return mmm_pairs_kernel<T, BW, 2, 4, 64, FUSED>;    // few rows: 128 columns, K in four shares
     case 2: return mmm_pairs_kernel<T, BW, 8, 2, 64, FUSED>;    // few rows, mask evaluated here: the predicate work is shared by 512 columns
+    case 3: return mmm_pairs_kernel<T, BW, 4, 4, 64, FUSED>;    // very few rows, mask evaluated here: one range of k per wave
     default: return mmm_pairs_kernel<T, BW, 8, 1, 64, FUSED>;   // 512 columns side by side
     }
 }
-constexpr PairsShape kShapes[] = {{8, 1}, {2, 4}, {8, 2}};
+constexpr PairsShape kShapes[] = {{8, 1}, {2, 4}, {8, 2}, {4, 4}};
 
 template <typename T, bool FUSED> pairs_kernel_fn pick(int32_t bw, int shape)
 {
@@ -382,7 +383,7 @@ hipError_t mmm_launch_pairs(const mmm_maps *m, int32_t dtype, const void *X, int
     // Workgroups of 8 waves x 64 columns; when that gives the machine too little to do (few rows:
     // the decode shape), fewer columns per workgroup and K shared out over several waves.
     const int64_t wide = (m->N + 511) / 512 * m->M;
-    const int shape = wide >= 1024 ? 0 : fused ? 2 : 1;
+    const int shape = wide >= 1024 ? 0 : !fused ? 1 : m->M <= 16 ? 3 : 2;
     const PairsShape sh = kShapes[shape];
     const int64_t span = sh.cw * 64;
     const int64_t ctiles = (m->N + span - 1) / span;
